@@ -1,0 +1,193 @@
+/*
+ * bmgd.h -- C ABI of the buffered mini-batch gradient descent (BMGD) library
+ * for one AMD Instinct MI355X (gfx950).
+ *
+ * The library implements the *computation step* of the paper's Algorithm 1
+ * (Section 2.2): a buffer of rows (X_i, Y_i) that already sits in GPU memory
+ * is swept for T passes; each pass starts with a fresh random partition of the
+ * buffer into mini-batches and then applies, strictly in order, the update of
+ * eq. (2.1)
+ *
+ *      theta <- theta - alpha * (1/n_b) * sum_{i in mini-batch} grad l(X_i, Y_i; theta)
+ *
+ * for least squares (Section 3.1, eq. (3.1)), logistic regression (Section
+ * 3.2.3 with b' = sigmoid, Section 4.1) or softmax regression (the C-class
+ * member of the same family).  The estimate left by one buffer is the start of
+ * the next (Section 2.2).  While one buffer is being computed on, the next one
+ * is copied host -> device into a second slot on another stream: the paper's
+ * "buffering step", which it wants executed fully in parallel (Section 2.1).
+ *
+ * The caller owns the loops over iterations r = 1..R and buffers k = 1..K of
+ * Algorithm 1: per buffer it calls bmgd_load_buffer_async() and then
+ * bmgd_run_buffer().  All work is enqueued on the caller's HIP streams; only
+ * bmgd_get_theta(), bmgd_get_perm(), bmgd_get_stats(), bmgd_sync() and
+ * bmgd_destroy() block the host.
+ *
+ * General rules
+ *   - Every function is extern "C", never throws and never aborts.  Except for
+ *     bmgd_create(), bmgd_workspace_bytes() and bmgd_last_error() they return a
+ *     status code; on failure bmgd_last_error() holds a message.
+ *   - A context belongs to one host thread at a time (no internal locking) and
+ *     to the HIP device that was current when it was created.
+ *   - "host" pointers are ordinary or pinned host memory, "device" pointers are
+ *     HIP device memory on the context's device.  Streams are hipStream_t
+ *     values passed as void* (NULL = the default stream).  Keep all streams at
+ *     the default priority.
+ *   - If no usable GPU is present every call that needs one fails with
+ *     BMGD_EHIP; there is no CPU fallback.
+ */
+#ifndef BMGD_H
+#define BMGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bmgd_ctx bmgd_ctx;
+
+/* status codes */
+enum {
+    BMGD_OK = 0,
+    BMGD_EINVAL = 1,    /* bad argument (also: a shape outside the supported range) */
+    BMGD_ESTATE = 2,    /* call out of order, e.g. run with nothing loaded */
+    BMGD_EHIP = 3,      /* a HIP call failed, no GPU, or a kernel reported a time-out */
+    BMGD_ENOMEM = 4     /* device or host allocation failed / workspace too small */
+};
+
+/* per-sample loss l (what grad l is) */
+enum {
+    BMGD_LINEAR = 0,    /* (x'theta - y) x            -- eq. (3.1) */
+    BMGD_LOGISTIC = 1,  /* (sigmoid(x'theta) - y) x   -- Section 3.2.3, y in {0,1} */
+    BMGD_SOFTMAX = 2    /* x (softmax(x'W) - onehot(y))', W is p x C row-major */
+};
+
+/* storage type of X */
+enum { BMGD_F32 = 0, BMGD_BF16 = 1 };
+
+/* how mini-batch partitions are drawn */
+enum {
+    BMGD_RESHUFFLE_PER_PASS = 0, /* Algorithm 1: a new partition for every pass of every buffer */
+    BMGD_RESHUFFLE_FIXED = 1     /* Section 3.1.1: one partition per buffer index k, reused for all r, t */
+};
+
+/* how the sequential chain of mini-batch steps is driven */
+enum {
+    BMGD_CHAIN_AUTO = 0,
+    BMGD_CHAIN_PERSISTENT = 1,   /* one cooperative kernel per buffer, grid-wide barrier per step */
+    BMGD_CHAIN_LAUNCH = 2        /* kernel launches per step, in stream order */
+};
+
+typedef struct bmgd_config {
+    int64_t  p;            /* features per row (> 0) */
+    int64_t  buffer_n;     /* N0: rows a slot can hold (> 0, < 2^30) */
+    int64_t  batch_n;      /* n: rows per mini-batch (1 <= n <= buffer_n); a short last batch is averaged
+                              over its own size */
+    double   lr;           /* alpha: finite, > 0 */
+    int32_t  passes;       /* T >= 1 */
+    int32_t  model;        /* BMGD_LINEAR / BMGD_LOGISTIC / BMGD_SOFTMAX */
+    int32_t  n_classes;    /* C >= 2 for softmax; ignored (treated as 1) otherwise */
+    int32_t  x_dtype;      /* BMGD_F32 (linear, logistic) or BMGD_BF16 (softmax) */
+    uint64_t seed;         /* seed of the partition generator */
+    int32_t  reshuffle;    /* BMGD_RESHUFFLE_* */
+    int32_t  n_buffers;    /* K; used only by BMGD_RESHUFFLE_FIXED (partition index = buffer counter mod K);
+                              0 = use the buffer counter itself */
+    int32_t  chain;        /* BMGD_CHAIN_* */
+    int32_t  n_workgroups; /* workgroups taking part in each step; 0 = chosen from the shape */
+    int64_t  barrier_timeout_us; /* upper bound on any single device-side wait; 0 = default (2 s).
+                              A wait that exceeds it makes the kernel exit and the next blocking call
+                              return BMGD_EHIP. */
+    void*    workspace;    /* optional device memory for everything the context needs on the device;
+                              NULL = the library allocates (and frees) it.  Must be 256-byte aligned and
+                              stay valid until bmgd_destroy(). */
+    size_t   workspace_bytes;
+} bmgd_config;
+
+typedef struct bmgd_stats {
+    int64_t buffers_run;       /* completed bmgd_run_* enqueues (= the buffer counter b) */
+    int64_t steps;             /* mini-batch updates enqueued so far */
+    int64_t sample_gradients;  /* rows visited, summed over steps */
+    int64_t h2d_bytes;         /* bytes handed to host->device copies by bmgd_load_buffer_async */
+    double  copy_ms;           /* device time spent in those copies (event-timed, completed ones) */
+    double  compute_ms;        /* device time spent in bmgd_run_* work (event-timed, completed ones) */
+    double  wait_ms;           /* part of copy time that compute had to wait for: sum over runs of the
+                                  time between "previous run finished (or this run was enqueued)" and
+                                  "this run's buffer finished loading", when positive */
+    int32_t n_workgroups;      /* launch shape in use */
+    int32_t threads_per_group;
+    int32_t chain;             /* resolved BMGD_CHAIN_* */
+    int32_t reserved;
+} bmgd_stats;
+
+/* Fill *cfg with defaults: linear model, fp32, 1 class, seed 0, per-pass reshuffle, automatic launch
+ * shape, library-owned memory.  p, buffer_n, batch_n, lr, passes are left 0 for the caller to set. */
+void bmgd_default_config(bmgd_config* cfg);
+
+/* Algorithm 1's inputs (alpha, M via batch_n, T) plus the buffer capacity.  Defaults as above, theta = 0.
+ * Returns NULL on failure (invalid argument, no GPU, out of memory). */
+bmgd_ctx* bmgd_create(int64_t p, int64_t buffer_n, int64_t batch_n, double lr, int passes);
+
+/* Full form.  *out receives the context.  Errors: BMGD_EINVAL (see field comments; also p above the
+ * supported maximum: 4096 if p % 4 == 0, 2048 if p % 2 == 0, else 1024 for the GLM models),
+ * BMGD_EHIP, BMGD_ENOMEM. */
+int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out);
+
+/* Device bytes a context with this configuration needs (two buffer slots, partitions, theta, scratch);
+ * 0 if the configuration is invalid.  Needs no GPU. */
+size_t bmgd_workspace_bytes(const bmgd_config* cfg);
+
+/* Buffering step (Section 2.1; Algorithm 1's "start preparing buffered data"): enqueue on copy_stream the
+ * copy of `rows` rows into the slot that is not being computed on.
+ *   host_x  host, row-major [rows][p], fp32 or bf16 per x_dtype.  Pinned memory is needed for the copy
+ *           to overlap with compute.
+ *   host_y  host, [rows]: fp32 responses (0/1 for logistic) or int32 class ids in [0, C) for softmax.
+ * The memory must stay valid and unchanged until the copy has completed (bmgd_sync, or a
+ * synchronisation of copy_stream by the caller).  The copy waits, on the device, for the run that last
+ * read the target slot.  At most one loaded-but-not-run buffer may exist: a second load without a run in
+ * between returns BMGD_ESTATE.  rows must satisfy 1 <= rows <= buffer_n. */
+int bmgd_load_buffer_async(bmgd_ctx* ctx, const void* host_x, const void* host_y, int64_t rows,
+                           void* copy_stream);
+
+/* Computation step on the most recently loaded buffer: enqueue on compute_stream T passes of sequential
+ * mini-batch updates (eq. (2.1)), after a device-side wait for that buffer's copy.  Partitions are
+ * PERM(seed, b, t, rows) for pass t = 1..T with b the number of buffers run before this one (or
+ * PERM(seed, b mod K, 0, rows) in fixed mode).  Returns BMGD_ESTATE if nothing is loaded. */
+int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream);
+
+/* Same computation step on a buffer that is already resident in device memory and owned by the caller
+ * (no copy, no slot): dev_x [rows][p], dev_y [rows], 256-byte aligned, valid until the work completes. */
+int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows,
+                           void* compute_stream);
+
+/* Wait for all enqueued work, then copy theta to host_out (fp32, p values; p*C row-major [p][C] for
+ * softmax).  len must equal that count.  This is Algorithm 1's output when called after the last buffer. */
+int bmgd_get_theta(bmgd_ctx* ctx, float* host_out, int64_t len);
+
+/* Wait for all enqueued work, then overwrite theta (the initial value of Algorithm 1, or a checkpoint). */
+int bmgd_set_theta(bmgd_ctx* ctx, const float* host_in, int64_t len);
+
+/* Set the buffer counter b (wait-free); with bmgd_set_theta this resumes a run exactly. */
+int bmgd_set_position(bmgd_ctx* ctx, int64_t buffer_counter);
+
+/* Parity hook: compute on the device, and copy to host_out, the partition PERM(seed, buffer_counter,
+ * pass, len) exactly as a run would use it (pass 0 = the fixed-mode partition).  Blocks. */
+int bmgd_get_perm(bmgd_ctx* ctx, int64_t buffer_counter, int pass, int32_t* host_out, int64_t len);
+
+/* Wait for all enqueued work (both streams last used) and report a device-side time-out if one happened. */
+int bmgd_sync(bmgd_ctx* ctx);
+
+/* Counters and event timings; blocks like bmgd_sync. */
+int bmgd_get_stats(bmgd_ctx* ctx, bmgd_stats* out);
+
+/* Message for the last failure on this context; with ctx == NULL, for the last failed bmgd_create*. */
+const char* bmgd_last_error(const bmgd_ctx* ctx);
+
+/* Wait for enqueued work and release everything the library allocated.  NULL is ignored. */
+void bmgd_destroy(bmgd_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BMGD_H */

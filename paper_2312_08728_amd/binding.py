@@ -1,0 +1,257 @@
+"""ctypes binding of libbmgd (see include/bmgd.h).
+
+Argument marshalling only: every step of the computation runs inside the
+library's HIP kernels.  The module-level ``bmgd_*`` functions mirror the C
+entry points one to one; ``Context`` is a small convenience wrapper around a
+``bmgd_ctx*`` that accepts numpy arrays and torch tensors (anything with a data
+pointer) and torch streams.  If the shared library has not been built the
+import fails loudly -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbmgd.so")
+
+BMGD_OK, BMGD_EINVAL, BMGD_ESTATE, BMGD_EHIP, BMGD_ENOMEM = 0, 1, 2, 3, 4
+BMGD_LINEAR, BMGD_LOGISTIC, BMGD_SOFTMAX = 0, 1, 2
+BMGD_F32, BMGD_BF16 = 0, 1
+BMGD_RESHUFFLE_PER_PASS, BMGD_RESHUFFLE_FIXED = 0, 1
+BMGD_CHAIN_AUTO, BMGD_CHAIN_PERSISTENT, BMGD_CHAIN_LAUNCH = 0, 1, 2
+
+EXPORTS = [
+    "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
+    "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_device_buffer", "bmgd_get_theta",
+    "bmgd_set_theta", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
+    "bmgd_last_error", "bmgd_destroy",
+]
+
+
+class bmgd_config(C.Structure):
+    _fields_ = [
+        ("p", C.c_int64), ("buffer_n", C.c_int64), ("batch_n", C.c_int64), ("lr", C.c_double),
+        ("passes", C.c_int32), ("model", C.c_int32), ("n_classes", C.c_int32), ("x_dtype", C.c_int32),
+        ("seed", C.c_uint64), ("reshuffle", C.c_int32), ("n_buffers", C.c_int32), ("chain", C.c_int32),
+        ("n_workgroups", C.c_int32), ("barrier_timeout_us", C.c_int64), ("workspace", C.c_void_p),
+        ("workspace_bytes", C.c_size_t),
+    ]
+
+
+class bmgd_stats(C.Structure):
+    _fields_ = [
+        ("buffers_run", C.c_int64), ("steps", C.c_int64), ("sample_gradients", C.c_int64),
+        ("h2d_bytes", C.c_int64), ("copy_ms", C.c_double), ("compute_ms", C.c_double),
+        ("wait_ms", C.c_double), ("n_workgroups", C.c_int32), ("threads_per_group", C.c_int32),
+        ("chain", C.c_int32), ("reserved", C.c_int32),
+    ]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2312_08728_amd.build "
+                          f"or __graft_entry__.build()); there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int
+    lib.bmgd_default_config.argtypes, lib.bmgd_default_config.restype = [C.POINTER(bmgd_config)], None
+    lib.bmgd_create.argtypes, lib.bmgd_create.restype = [i64, i64, i64, C.c_double, i32], vp
+    lib.bmgd_create_ex.argtypes, lib.bmgd_create_ex.restype = [C.POINTER(bmgd_config), C.POINTER(vp)], i32
+    lib.bmgd_workspace_bytes.argtypes, lib.bmgd_workspace_bytes.restype = [C.POINTER(bmgd_config)], C.c_size_t
+    lib.bmgd_load_buffer_async.argtypes, lib.bmgd_load_buffer_async.restype = [vp, vp, vp, i64, vp], i32
+    lib.bmgd_run_buffer.argtypes, lib.bmgd_run_buffer.restype = [vp, vp], i32
+    lib.bmgd_run_device_buffer.argtypes, lib.bmgd_run_device_buffer.restype = [vp, vp, vp, i64, vp], i32
+    lib.bmgd_get_theta.argtypes, lib.bmgd_get_theta.restype = [vp, vp, i64], i32
+    lib.bmgd_set_theta.argtypes, lib.bmgd_set_theta.restype = [vp, vp, i64], i32
+    lib.bmgd_set_position.argtypes, lib.bmgd_set_position.restype = [vp, i64], i32
+    lib.bmgd_get_perm.argtypes, lib.bmgd_get_perm.restype = [vp, i64, i32, vp, i64], i32
+    lib.bmgd_sync.argtypes, lib.bmgd_sync.restype = [vp], i32
+    lib.bmgd_get_stats.argtypes, lib.bmgd_get_stats.restype = [vp, C.POINTER(bmgd_stats)], i32
+    lib.bmgd_last_error.argtypes, lib.bmgd_last_error.restype = [vp], C.c_char_p
+    lib.bmgd_destroy.argtypes, lib.bmgd_destroy.restype = [vp], None
+    return lib
+
+
+lib = _load()
+
+
+def _ptr(a) -> int:
+    """Address of a numpy array, torch tensor, ctypes buffer or raw int."""
+    if a is None:
+        return 0
+    if isinstance(a, int):
+        return a
+    if isinstance(a, np.ndarray):
+        if not a.flags["C_CONTIGUOUS"]:
+            raise ValueError("array must be C-contiguous")
+        return a.ctypes.data
+    if hasattr(a, "data_ptr"):
+        if not a.is_contiguous():
+            raise ValueError("tensor must be contiguous")
+        return a.data_ptr()
+    return C.addressof(a)
+
+
+def _stream(s) -> int:
+    if s is None:
+        return 0
+    if isinstance(s, int):
+        return s
+    return int(s.cuda_stream)
+
+
+# ---- one-to-one mirrors of the C entry points -------------------------------------------------
+def bmgd_default_config() -> bmgd_config:
+    cfg = bmgd_config()
+    lib.bmgd_default_config(C.byref(cfg))
+    return cfg
+
+
+def bmgd_create(p, buffer_n, batch_n, lr, passes):
+    return lib.bmgd_create(p, buffer_n, batch_n, lr, passes)
+
+
+def bmgd_create_ex(cfg: bmgd_config):
+    out = C.c_void_p()
+    rc = lib.bmgd_create_ex(C.byref(cfg), C.byref(out))
+    return rc, out.value
+
+
+def bmgd_workspace_bytes(cfg: bmgd_config) -> int:
+    return lib.bmgd_workspace_bytes(C.byref(cfg))
+
+
+def bmgd_load_buffer_async(ctx, host_x, host_y, rows, copy_stream=None) -> int:
+    return lib.bmgd_load_buffer_async(ctx, _ptr(host_x), _ptr(host_y), rows, _stream(copy_stream))
+
+
+def bmgd_run_buffer(ctx, compute_stream=None) -> int:
+    return lib.bmgd_run_buffer(ctx, _stream(compute_stream))
+
+
+def bmgd_run_device_buffer(ctx, dev_x, dev_y, rows, compute_stream=None) -> int:
+    return lib.bmgd_run_device_buffer(ctx, _ptr(dev_x), _ptr(dev_y), rows, _stream(compute_stream))
+
+
+def bmgd_get_theta(ctx, host_out, length) -> int:
+    return lib.bmgd_get_theta(ctx, _ptr(host_out), length)
+
+
+def bmgd_set_theta(ctx, host_in, length) -> int:
+    return lib.bmgd_set_theta(ctx, _ptr(host_in), length)
+
+
+def bmgd_set_position(ctx, buffer_counter) -> int:
+    return lib.bmgd_set_position(ctx, buffer_counter)
+
+
+def bmgd_get_perm(ctx, buffer_counter, pass_, host_out, length) -> int:
+    return lib.bmgd_get_perm(ctx, buffer_counter, pass_, _ptr(host_out), length)
+
+
+def bmgd_sync(ctx) -> int:
+    return lib.bmgd_sync(ctx)
+
+
+def bmgd_get_stats(ctx):
+    st = bmgd_stats()
+    rc = lib.bmgd_get_stats(ctx, C.byref(st))
+    return rc, st
+
+
+def bmgd_last_error(ctx=None) -> str:
+    msg = lib.bmgd_last_error(ctx)
+    return msg.decode() if msg else ""
+
+
+def bmgd_destroy(ctx) -> None:
+    lib.bmgd_destroy(ctx)
+
+
+# ---- convenience wrapper ------------------------------------------------------------------------
+class BmgdError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"bmgd status {code}: {msg}")
+        self.code = code
+
+
+class Context:
+    """Owns one bmgd_ctx*; raises BmgdError on any non-OK status."""
+
+    def __init__(self, p, buffer_n, batch_n, lr, passes, model=BMGD_LINEAR, n_classes=1, x_dtype=None,
+                 seed=0, reshuffle=BMGD_RESHUFFLE_PER_PASS, n_buffers=0, chain=BMGD_CHAIN_AUTO,
+                 n_workgroups=0, barrier_timeout_us=0, workspace=None, workspace_bytes=0):
+        cfg = bmgd_default_config()
+        cfg.p, cfg.buffer_n, cfg.batch_n, cfg.lr, cfg.passes = p, buffer_n, batch_n, lr, passes
+        cfg.model, cfg.n_classes = model, n_classes
+        cfg.x_dtype = (BMGD_BF16 if model == BMGD_SOFTMAX else BMGD_F32) if x_dtype is None else x_dtype
+        cfg.seed, cfg.reshuffle, cfg.n_buffers = seed, reshuffle, n_buffers
+        cfg.chain, cfg.n_workgroups, cfg.barrier_timeout_us = chain, n_workgroups, barrier_timeout_us
+        if workspace is not None:
+            cfg.workspace, cfg.workspace_bytes = _ptr(workspace), workspace_bytes
+        self.cfg = cfg
+        self.theta_len = p * (n_classes if model == BMGD_SOFTMAX else 1)
+        self._keep = workspace
+        rc, h = bmgd_create_ex(cfg)
+        if rc != BMGD_OK:
+            raise BmgdError(rc, bmgd_last_error(None))
+        self.h = h
+
+    def _check(self, rc):
+        if rc != BMGD_OK:
+            raise BmgdError(rc, bmgd_last_error(self.h))
+
+    def load_buffer_async(self, host_x, host_y, rows, copy_stream=None):
+        self._check(bmgd_load_buffer_async(self.h, host_x, host_y, rows, copy_stream))
+
+    def run_buffer(self, compute_stream=None):
+        self._check(bmgd_run_buffer(self.h, compute_stream))
+
+    def run_device_buffer(self, dev_x, dev_y, rows, compute_stream=None):
+        self._check(bmgd_run_device_buffer(self.h, dev_x, dev_y, rows, compute_stream))
+
+    def get_theta(self) -> np.ndarray:
+        out = np.empty(self.theta_len, dtype=np.float32)
+        self._check(bmgd_get_theta(self.h, out, out.size))
+        if self.cfg.model == BMGD_SOFTMAX:
+            return out.reshape(self.cfg.p, self.cfg.n_classes)
+        return out
+
+    def set_theta(self, theta):
+        a = np.ascontiguousarray(theta, dtype=np.float32).reshape(-1)
+        self._check(bmgd_set_theta(self.h, a, a.size))
+
+    def set_position(self, buffer_counter):
+        self._check(bmgd_set_position(self.h, buffer_counter))
+
+    def get_perm(self, buffer_counter, pass_, length) -> np.ndarray:
+        out = np.empty(length, dtype=np.int32)
+        self._check(bmgd_get_perm(self.h, buffer_counter, pass_, out, length))
+        return out
+
+    def sync(self):
+        self._check(bmgd_sync(self.h))
+
+    def stats(self) -> bmgd_stats:
+        rc, st = bmgd_get_stats(self.h)
+        self._check(rc)
+        return st
+
+    def close(self):
+        if getattr(self, "h", None):
+            bmgd_destroy(self.h)
+            self.h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,545 @@
+// Host side of libbmgd: contexts, the two-slot buffer state machine, stream/event ordering between the
+// buffering step and the computation step (Section 2.1), and the C ABI declared in include/bmgd.h.
+#include "../../include/bmgd.h"
+#include "bmgd_internal.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace bmgd;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+constexpr size_t kAlign = 256;
+constexpr int kMaxGroups = 256;                    // upper bound used to size the partial-sum scratch
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t slot_x[2], slot_y[2], perm, theta, partial, sync, aux, total;
+};
+
+struct Slot {
+    void* x = nullptr;
+    void* y = nullptr;
+    int64_t rows = 0;
+    hipEvent_t copy_done = nullptr;                // recorded on the copy stream after the slot is filled
+    hipEvent_t compute_done = nullptr;             // recorded on the compute stream after the slot was read
+    bool was_read = false;
+};
+
+struct RunRecord {                                 // event quintet of one buffer, for the overlap statistics
+    hipEvent_t copy_start = nullptr, copy_end = nullptr, ready = nullptr, start = nullptr, end = nullptr;
+    bool has_copy = false;
+};
+
+}  // namespace
+
+struct bmgd_ctx {
+    bmgd_config cfg{};
+    int device = 0;
+    int num_cus = 0;
+    int64_t theta_len = 0;
+    size_t x_itemsize = 4;
+    void* ws = nullptr;
+    bool owns_ws = false;
+    Layout lay{};
+    Slot slots[2];
+    int next_slot = 0;                             // slot the next load goes to
+    int pending = -1;                              // slot loaded but not yet run
+    int32_t* perm = nullptr;
+    float* theta = nullptr;
+    float* partial = nullptr;
+    unsigned* sync = nullptr;
+    GlmLaunchShape shape{};
+    int chain = BMGD_CHAIN_PERSISTENT;
+    int64_t buffer_counter = 0;
+    int64_t steps = 0, sample_gradients = 0, h2d_bytes = 0;
+    double copy_ms = 0, compute_ms = 0, wait_ms = 0;
+    hipEvent_t base = nullptr;
+    std::vector<RunRecord> open_records;
+    std::vector<hipEvent_t> event_pool;
+    RunRecord pending_copy;                        // copy events of the buffer that is loaded but not run
+    hipStream_t last_copy = nullptr, last_compute = nullptr;
+    bool used_copy = false, used_compute = false;
+    std::string err;
+};
+
+namespace {
+
+bool valid_config(const bmgd_config& c, std::string* why)
+{
+    auto bad = [&](const char* m) { *why = m; return false; };
+    if (c.p <= 0) return bad("p must be positive");
+    if (c.buffer_n <= 0 || c.buffer_n >= (int64_t(1) << 30)) return bad("buffer_n must be in [1, 2^30)");
+    if (c.batch_n <= 0 || c.batch_n > c.buffer_n) return bad("batch_n must be in [1, buffer_n]");
+    if (!(c.lr > 0.0) || !std::isfinite(c.lr)) return bad("lr must be finite and positive");
+    if (c.passes < 1) return bad("passes must be at least 1");
+    if (c.model != BMGD_LINEAR && c.model != BMGD_LOGISTIC && c.model != BMGD_SOFTMAX) return bad("unknown model");
+    if (c.model == BMGD_SOFTMAX) {
+        if (c.n_classes < 2) return bad("softmax needs n_classes >= 2");
+        if (c.x_dtype != BMGD_BF16) return bad("softmax takes bf16 predictors");
+    } else if (c.x_dtype != BMGD_F32) {
+        return bad("linear and logistic models take fp32 predictors");
+    }
+    if (c.reshuffle != BMGD_RESHUFFLE_PER_PASS && c.reshuffle != BMGD_RESHUFFLE_FIXED) return bad("unknown reshuffle mode");
+    if (c.n_buffers < 0) return bad("n_buffers must be non-negative");
+    if (c.chain != BMGD_CHAIN_AUTO && c.chain != BMGD_CHAIN_PERSISTENT && c.chain != BMGD_CHAIN_LAUNCH)
+        return bad("unknown chain mode");
+    if (c.n_workgroups < 0 || c.n_workgroups > kMaxGroups) return bad("n_workgroups must be in [0, 256]");
+    if (c.barrier_timeout_us < 0) return bad("barrier_timeout_us must be non-negative");
+    if (c.workspace != nullptr && (reinterpret_cast<uintptr_t>(c.workspace) % kAlign) != 0)
+        return bad("workspace must be 256-byte aligned");
+    if (c.model != BMGD_SOFTMAX) {
+        GlmLaunchShape s;
+        char msg[160];
+        if (!glm_plan(c.p, c.batch_n, c.n_workgroups, kMaxGroups, &s, msg, sizeof msg)) {
+            *why = msg;
+            return false;
+        }
+    }
+    if ((double)c.buffer_n * (double)c.p > 9.0e18 / 8) return bad("buffer too large");
+    return true;
+}
+
+Layout make_layout(const bmgd_config& c)
+{
+    Layout l{};
+    const size_t item = c.x_dtype == BMGD_BF16 ? 2 : 4;
+    const int64_t C = c.model == BMGD_SOFTMAX ? c.n_classes : 1;
+    size_t off = 0;
+    for (int s = 0; s < 2; ++s) {
+        l.slot_x[s] = off; off += align_up((size_t)c.buffer_n * c.p * item);
+        l.slot_y[s] = off; off += align_up((size_t)c.buffer_n * 4);
+    }
+    const int np = std::min<int>(c.passes, kMaxPassesPerLaunch);
+    l.perm = off;    off += align_up((size_t)np * c.buffer_n * 4);
+    l.theta = off;   off += align_up((size_t)c.p * C * 4);
+    l.partial = off; off += align_up((size_t)2 * kMaxGroups * c.p * 4);
+    l.sync = off;    off += align_up(64);
+    l.aux = off;
+    l.total = off;
+    return l;
+}
+
+int fail(bmgd_ctx* ctx, int code, const std::string& msg)
+{
+    if (ctx) ctx->err = msg; else g_create_error = msg;
+    return code;
+}
+
+int hip_fail(bmgd_ctx* ctx, hipError_t e, const char* what)
+{
+    char buf[256];
+    snprintf(buf, sizeof buf, "%s: %s", what, hipGetErrorString(e));
+    (void)hipGetLastError();
+    return fail(ctx, e == hipErrorOutOfMemory ? BMGD_ENOMEM : BMGD_EHIP, buf);
+}
+
+#define HIP_TRY(ctx, call)                                              \
+    do {                                                                \
+        hipError_t e_ = (call);                                         \
+        if (e_ != hipSuccess) return hip_fail((ctx), e_, #call);        \
+    } while (0)
+
+hipEvent_t take_event(bmgd_ctx* ctx)
+{
+    if (!ctx->event_pool.empty()) {
+        hipEvent_t e = ctx->event_pool.back();
+        ctx->event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void give_event(bmgd_ctx* ctx, hipEvent_t e) { if (e) ctx->event_pool.push_back(e); }
+
+// Fold finished runs into the running totals.  Call only after both streams have drained.
+void settle_records(bmgd_ctx* ctx)
+{
+    for (RunRecord& r : ctx->open_records) {
+        float ms = 0.f, t_ready = 0.f, t_start = 0.f;
+        if (hipEventElapsedTime(&ms, r.start, r.end) == hipSuccess) ctx->compute_ms += ms;
+        if (r.has_copy) {
+            if (hipEventElapsedTime(&ms, r.copy_start, r.copy_end) == hipSuccess) ctx->copy_ms += ms;
+            // time the compute stream sat at "buffer not loaded yet"
+            if (hipEventElapsedTime(&t_ready, ctx->base, r.ready) == hipSuccess &&
+                hipEventElapsedTime(&t_start, ctx->base, r.start) == hipSuccess && t_start > t_ready)
+                ctx->wait_ms += t_start - t_ready;
+        }
+        give_event(ctx, r.copy_start); give_event(ctx, r.copy_end);
+        give_event(ctx, r.ready); give_event(ctx, r.start); give_event(ctx, r.end);
+    }
+    ctx->open_records.clear();
+}
+
+int drain(bmgd_ctx* ctx)
+{
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    if (ctx->used_copy) HIP_TRY(ctx, hipStreamSynchronize(ctx->last_copy));
+    if (ctx->used_compute) HIP_TRY(ctx, hipStreamSynchronize(ctx->last_compute));
+    settle_records(ctx);
+    unsigned flag = 0;
+    HIP_TRY(ctx, hipMemcpy(&flag, ctx->sync + 1, sizeof flag, hipMemcpyDeviceToHost));
+    if (flag != 0) {
+        HIP_TRY(ctx, hipMemset(ctx->sync, 0, 64));
+        return fail(ctx, BMGD_EHIP, "a device-side wait exceeded barrier_timeout_us; the run was abandoned and theta is not valid");
+    }
+    return BMGD_OK;
+}
+
+int64_t batches_of(int64_t rows, int64_t n) { return (rows + n - 1) / n; }
+
+// Enqueue T passes over (x, y, rows) on `stream`.
+int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hipStream_t stream)
+{
+    const bmgd_config& c = ctx->cfg;
+    const int64_t n = std::min<int64_t>(c.batch_n, rows);
+    const int64_t M = batches_of(rows, n);
+    const bool fixed = c.reshuffle == BMGD_RESHUFFLE_FIXED;
+    const uint32_t b = (uint32_t)(fixed && c.n_buffers > 0 ? ctx->buffer_counter % c.n_buffers : ctx->buffer_counter);
+    const long long ticks = (c.barrier_timeout_us > 0 ? c.barrier_timeout_us : 2000000) * 100LL;
+
+    for (int t0 = 0; t0 < c.passes; t0 += kMaxPassesPerLaunch) {
+        const int np = std::min(kMaxPassesPerLaunch, c.passes - t0);
+        PermKeys keys{};
+        const int nperm = fixed ? 1 : np;
+        if (!fixed || t0 == 0) {
+            for (int i = 0; i < nperm; ++i) perm_round_keys(c.seed, b, fixed ? 0u : (uint32_t)(t0 + i + 1), keys.key[i]);
+            HIP_TRY(ctx, launch_perm(ctx->perm, rows, nperm, keys, stream));
+        }
+        GlmArgs a{};
+        a.X = static_cast<const float*>(x);
+        a.y = static_cast<const float*>(y);
+        a.perm = ctx->perm;
+        a.theta = ctx->theta;
+        a.partial = ctx->partial;
+        a.sync = ctx->sync;
+        a.rows = (int)rows; a.p = (int)c.p; a.n = (int)n; a.npass = np;
+        a.perm_stride = fixed ? 0 : (int)rows;
+        a.model = c.model;
+        a.L = ctx->shape.L;
+        a.logL = 0;
+        while ((1 << a.logL) < a.L) ++a.logL;
+        a.reduce_mode = ctx->shape.reduce_mode;
+        a.alpha = (float)c.lr;
+        a.timeout_ticks = ticks;
+        a.single_step = -1;
+        if ((double)np * (double)M * 2.0 * ctx->shape.G > 4.0e9)
+            return fail(ctx, BMGD_EINVAL, "too many steps per launch for the barrier counter");
+        if (ctx->chain == BMGD_CHAIN_PERSISTENT) {
+            HIP_TRY(ctx, hipMemsetAsync(ctx->sync, 0, sizeof(unsigned), stream));
+            HIP_TRY(ctx, glm_launch_chain(ctx->shape, a, stream));
+        } else {
+            for (int64_t s = 0; s < (int64_t)np * M; ++s) {
+                a.single_step = (int)s;
+                const int64_t m = s % M;
+                const int nb = (int)std::min<int64_t>(n, rows - m * n);
+                HIP_TRY(ctx, glm_launch_step(ctx->shape, a, nb, stream));
+            }
+        }
+    }
+    ctx->steps += (int64_t)c.passes * M;
+    ctx->sample_gradients += (int64_t)c.passes * rows;
+    ctx->buffer_counter += 1;
+    return BMGD_OK;
+}
+
+void destroy_ctx(bmgd_ctx* ctx)
+{
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    if (ctx->used_copy) (void)hipStreamSynchronize(ctx->last_copy);
+    if (ctx->used_compute) (void)hipStreamSynchronize(ctx->last_compute);
+    settle_records(ctx);
+    give_event(ctx, ctx->pending_copy.copy_start);
+    give_event(ctx, ctx->pending_copy.copy_end);
+    for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+    for (Slot& s : ctx->slots) {
+        if (s.copy_done) (void)hipEventDestroy(s.copy_done);
+        if (s.compute_done) (void)hipEventDestroy(s.compute_done);
+    }
+    if (ctx->base) (void)hipEventDestroy(ctx->base);
+    if (ctx->owns_ws && ctx->ws) (void)hipFree(ctx->ws);
+    delete ctx;
+}
+
+}  // namespace
+
+#define BMGD_API __attribute__((visibility("default")))
+
+extern "C" {
+
+BMGD_API void bmgd_default_config(bmgd_config* cfg)
+{
+    if (!cfg) return;
+    memset(cfg, 0, sizeof *cfg);
+    cfg->model = BMGD_LINEAR;
+    cfg->n_classes = 1;
+    cfg->x_dtype = BMGD_F32;
+    cfg->reshuffle = BMGD_RESHUFFLE_PER_PASS;
+    cfg->chain = BMGD_CHAIN_AUTO;
+}
+
+BMGD_API size_t bmgd_workspace_bytes(const bmgd_config* cfg)
+{
+    std::string why;
+    if (!cfg || !valid_config(*cfg, &why)) return 0;
+    return make_layout(*cfg).total;
+}
+
+BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
+{
+    if (out) *out = nullptr;
+    if (!cfg || !out) return fail(nullptr, BMGD_EINVAL, "cfg and out must not be NULL");
+    std::string why;
+    if (!valid_config(*cfg, &why)) return fail(nullptr, BMGD_EINVAL, why);
+    if (cfg->model == BMGD_SOFTMAX) return fail(nullptr, BMGD_EINVAL, "softmax is not available in this build of the library");
+
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev == 0) {
+        (void)hipGetLastError();
+        return fail(nullptr, BMGD_EHIP, "no HIP device available");
+    }
+    bmgd_ctx* ctx = new (std::nothrow) bmgd_ctx();
+    if (!ctx) return fail(nullptr, BMGD_ENOMEM, "out of host memory");
+    ctx->cfg = *cfg;
+    if (ctx->cfg.model != BMGD_SOFTMAX) ctx->cfg.n_classes = 1;
+    ctx->x_itemsize = cfg->x_dtype == BMGD_BF16 ? 2 : 4;
+    ctx->theta_len = cfg->p * ctx->cfg.n_classes;
+    ctx->lay = make_layout(ctx->cfg);
+
+    auto bail = [&](int code) {
+        g_create_error = ctx->err;
+        destroy_ctx(ctx);
+        return code;
+    };
+#define CREATE_TRY(call)                                                  \
+    do {                                                                  \
+        hipError_t e_ = (call);                                           \
+        if (e_ != hipSuccess) return bail(hip_fail(ctx, e_, #call));      \
+    } while (0)
+
+    CREATE_TRY(hipGetDevice(&ctx->device));
+    hipDeviceProp_t prop;
+    CREATE_TRY(hipGetDeviceProperties(&prop, ctx->device));
+    ctx->num_cus = prop.multiProcessorCount;
+    if (cfg->workspace) {
+        if (cfg->workspace_bytes < ctx->lay.total) {
+            ctx->err = "workspace smaller than bmgd_workspace_bytes()";
+            return bail(BMGD_ENOMEM);
+        }
+        ctx->ws = cfg->workspace;
+    } else {
+        CREATE_TRY(hipMalloc(&ctx->ws, ctx->lay.total));
+        ctx->owns_ws = true;
+    }
+    char* base = static_cast<char*>(ctx->ws);
+    for (int s = 0; s < 2; ++s) {
+        ctx->slots[s].x = base + ctx->lay.slot_x[s];
+        ctx->slots[s].y = base + ctx->lay.slot_y[s];
+        CREATE_TRY(hipEventCreate(&ctx->slots[s].copy_done));
+        CREATE_TRY(hipEventCreate(&ctx->slots[s].compute_done));
+    }
+    ctx->perm = reinterpret_cast<int32_t*>(base + ctx->lay.perm);
+    ctx->theta = reinterpret_cast<float*>(base + ctx->lay.theta);
+    ctx->partial = reinterpret_cast<float*>(base + ctx->lay.partial);
+    ctx->sync = reinterpret_cast<unsigned*>(base + ctx->lay.sync);
+    CREATE_TRY(hipMemset(ctx->theta, 0, (size_t)ctx->theta_len * 4));
+    CREATE_TRY(hipMemset(ctx->sync, 0, 64));
+    CREATE_TRY(hipEventCreate(&ctx->base));
+    CREATE_TRY(hipEventRecord(ctx->base, nullptr));
+
+    char msg[160];
+    if (!glm_plan(cfg->p, cfg->batch_n, cfg->n_workgroups, ctx->num_cus, &ctx->shape, msg, sizeof msg)) {
+        ctx->err = msg;
+        return bail(BMGD_EINVAL);
+    }
+    CREATE_TRY(glm_prepare(&ctx->shape));
+    ctx->chain = cfg->chain == BMGD_CHAIN_AUTO ? BMGD_CHAIN_PERSISTENT : cfg->chain;
+    CREATE_TRY(hipDeviceSynchronize());
+#undef CREATE_TRY
+    *out = ctx;
+    return BMGD_OK;
+}
+
+BMGD_API bmgd_ctx* bmgd_create(int64_t p, int64_t buffer_n, int64_t batch_n, double lr, int passes)
+{
+    bmgd_config cfg;
+    bmgd_default_config(&cfg);
+    cfg.p = p; cfg.buffer_n = buffer_n; cfg.batch_n = batch_n; cfg.lr = lr; cfg.passes = passes;
+    bmgd_ctx* ctx = nullptr;
+    if (bmgd_create_ex(&cfg, &ctx) != BMGD_OK) return nullptr;
+    return ctx;
+}
+
+BMGD_API int bmgd_load_buffer_async(bmgd_ctx* ctx, const void* host_x, const void* host_y, int64_t rows, void* copy_stream)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!host_x || !host_y) return fail(ctx, BMGD_EINVAL, "host_x and host_y must not be NULL");
+    if (rows < 1 || rows > ctx->cfg.buffer_n) return fail(ctx, BMGD_EINVAL, "rows must be in [1, buffer_n]");
+    if (ctx->pending >= 0) return fail(ctx, BMGD_ESTATE, "a buffer is already loaded and has not been run");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t cs = static_cast<hipStream_t>(copy_stream);
+    Slot& slot = ctx->slots[ctx->next_slot];
+    // the copy must not overwrite rows a run is still reading
+    if (slot.was_read) HIP_TRY(ctx, hipStreamWaitEvent(cs, slot.compute_done, 0));
+    RunRecord& rec = ctx->pending_copy;
+    if (!rec.copy_start) rec.copy_start = take_event(ctx);
+    if (!rec.copy_end) rec.copy_end = take_event(ctx);
+    if (!rec.copy_start || !rec.copy_end) return fail(ctx, BMGD_EHIP, "could not create events");
+    const size_t xbytes = (size_t)rows * ctx->cfg.p * ctx->x_itemsize, ybytes = (size_t)rows * 4;
+    HIP_TRY(ctx, hipEventRecord(rec.copy_start, cs));
+    HIP_TRY(ctx, hipMemcpyAsync(slot.x, host_x, xbytes, hipMemcpyHostToDevice, cs));
+    HIP_TRY(ctx, hipMemcpyAsync(slot.y, host_y, ybytes, hipMemcpyHostToDevice, cs));
+    HIP_TRY(ctx, hipEventRecord(rec.copy_end, cs));
+    HIP_TRY(ctx, hipEventRecord(slot.copy_done, cs));
+    rec.has_copy = true;
+    slot.rows = rows;
+    ctx->h2d_bytes += (int64_t)(xbytes + ybytes);
+    ctx->pending = ctx->next_slot;
+    ctx->next_slot ^= 1;
+    ctx->last_copy = cs;
+    ctx->used_copy = true;
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (ctx->pending < 0) return fail(ctx, BMGD_ESTATE, "no buffer is loaded");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(compute_stream);
+    Slot& slot = ctx->slots[ctx->pending];
+    RunRecord rec = ctx->pending_copy;
+    rec.ready = take_event(ctx); rec.start = take_event(ctx); rec.end = take_event(ctx);
+    if (!rec.ready || !rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
+    HIP_TRY(ctx, hipEventRecord(rec.ready, s));
+    HIP_TRY(ctx, hipStreamWaitEvent(s, slot.copy_done, 0));       // never read a slot that is still filling
+    HIP_TRY(ctx, hipEventRecord(rec.start, s));
+    const int rc = enqueue_compute(ctx, slot.x, slot.y, slot.rows, s);
+    ctx->last_compute = s;
+    ctx->used_compute = true;
+    if (rc != BMGD_OK) return rc;
+    HIP_TRY(ctx, hipEventRecord(rec.end, s));
+    HIP_TRY(ctx, hipEventRecord(slot.compute_done, s));
+    slot.was_read = true;
+    ctx->open_records.push_back(rec);
+    ctx->pending_copy = RunRecord();
+    ctx->pending = -1;
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* compute_stream)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!dev_x || !dev_y) return fail(ctx, BMGD_EINVAL, "dev_x and dev_y must not be NULL");
+    if (rows < 1 || rows >= (int64_t(1) << 30)) return fail(ctx, BMGD_EINVAL, "rows must be in [1, 2^30)");
+    if (rows > ctx->cfg.buffer_n) return fail(ctx, BMGD_EINVAL, "rows must not exceed buffer_n");
+    if ((reinterpret_cast<uintptr_t>(dev_x) % 16) != 0 || (reinterpret_cast<uintptr_t>(dev_y) % 4) != 0)
+        return fail(ctx, BMGD_EINVAL, "device buffers must be at least 16-byte aligned");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(compute_stream);
+    RunRecord rec;
+    rec.ready = take_event(ctx); rec.start = take_event(ctx); rec.end = take_event(ctx);
+    if (!rec.ready || !rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
+    HIP_TRY(ctx, hipEventRecord(rec.ready, s));
+    HIP_TRY(ctx, hipEventRecord(rec.start, s));
+    const int rc = enqueue_compute(ctx, dev_x, dev_y, rows, s);
+    ctx->last_compute = s;
+    ctx->used_compute = true;
+    if (rc != BMGD_OK) return rc;
+    HIP_TRY(ctx, hipEventRecord(rec.end, s));
+    ctx->open_records.push_back(rec);
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_sync(bmgd_ctx* ctx)
+{
+    if (!ctx) return BMGD_EINVAL;
+    return drain(ctx);
+}
+
+BMGD_API int bmgd_get_theta(bmgd_ctx* ctx, float* host_out, int64_t len)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!host_out) return fail(ctx, BMGD_EINVAL, "host_out must not be NULL");
+    if (len != ctx->theta_len) return fail(ctx, BMGD_EINVAL, "len must equal p (p * n_classes for softmax)");
+    const int rc = drain(ctx);
+    if (rc != BMGD_OK) return rc;
+    HIP_TRY(ctx, hipMemcpy(host_out, ctx->theta, (size_t)len * 4, hipMemcpyDeviceToHost));
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_set_theta(bmgd_ctx* ctx, const float* host_in, int64_t len)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!host_in) return fail(ctx, BMGD_EINVAL, "host_in must not be NULL");
+    if (len != ctx->theta_len) return fail(ctx, BMGD_EINVAL, "len must equal p (p * n_classes for softmax)");
+    const int rc = drain(ctx);
+    if (rc != BMGD_OK) return rc;
+    HIP_TRY(ctx, hipMemcpy(ctx->theta, host_in, (size_t)len * 4, hipMemcpyHostToDevice));
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_set_position(bmgd_ctx* ctx, int64_t buffer_counter)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (buffer_counter < 0 || buffer_counter > 0xFFFFFFFFLL) return fail(ctx, BMGD_EINVAL, "buffer_counter out of range");
+    ctx->buffer_counter = buffer_counter;
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_get_perm(bmgd_ctx* ctx, int64_t buffer_counter, int pass, int32_t* host_out, int64_t len)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!host_out) return fail(ctx, BMGD_EINVAL, "host_out must not be NULL");
+    if (len < 1 || len > ctx->cfg.buffer_n) return fail(ctx, BMGD_EINVAL, "len must be in [1, buffer_n]");
+    if (pass < 0 || buffer_counter < 0 || buffer_counter > 0xFFFFFFFFLL) return fail(ctx, BMGD_EINVAL, "bad pass or buffer_counter");
+    const int rc = drain(ctx);
+    if (rc != BMGD_OK) return rc;
+    PermKeys keys{};
+    perm_round_keys(ctx->cfg.seed, (uint32_t)buffer_counter, (uint32_t)pass, keys.key[0]);
+    HIP_TRY(ctx, launch_perm(ctx->perm, len, 1, keys, nullptr));
+    HIP_TRY(ctx, hipMemcpy(host_out, ctx->perm, (size_t)len * 4, hipMemcpyDeviceToHost));
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_get_stats(bmgd_ctx* ctx, bmgd_stats* out)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!out) return fail(ctx, BMGD_EINVAL, "out must not be NULL");
+    const int rc = drain(ctx);
+    memset(out, 0, sizeof *out);
+    out->buffers_run = ctx->buffer_counter;
+    out->steps = ctx->steps;
+    out->sample_gradients = ctx->sample_gradients;
+    out->h2d_bytes = ctx->h2d_bytes;
+    out->copy_ms = ctx->copy_ms;
+    out->compute_ms = ctx->compute_ms;
+    out->wait_ms = ctx->wait_ms;
+    out->n_workgroups = ctx->shape.G;
+    out->threads_per_group = ctx->shape.block;
+    out->chain = ctx->chain;
+    return rc;
+}
+
+BMGD_API const char* bmgd_last_error(const bmgd_ctx* ctx)
+{
+    return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+BMGD_API void bmgd_destroy(bmgd_ctx* ctx) { destroy_ctx(ctx); }
+
+}  // extern "C"

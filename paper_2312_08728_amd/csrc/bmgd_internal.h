@@ -1,0 +1,69 @@
+// Internal interfaces between the host-side context code and the HIP kernels of libbmgd.
+// Nothing here is part of the public ABI (see include/bmgd.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bmgd {
+
+constexpr int kPermRounds = 8;
+constexpr int kMaxPassesPerLaunch = 4;     // partitions kept on the device at a time
+
+// Round keys of the partition generator for up to kMaxPassesPerLaunch passes.
+struct PermKeys {
+    uint32_t key[kMaxPassesPerLaunch][kPermRounds];
+};
+
+// Host: derive the eight round keys of PERM(seed, b, t, .).
+void perm_round_keys(uint64_t seed, uint32_t b, uint32_t t, uint32_t out[kPermRounds]);
+// Host: half block width h of the Feistel network for a buffer of `rows` rows.
+int perm_half_width(int64_t rows);
+
+// Device: out[pass][j] = PERM(...)[j] for j < rows, pass < npass (row stride = rows).
+hipError_t launch_perm(int32_t* out, int64_t rows, int npass, const PermKeys& keys, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------------------
+// GLM (least squares / logistic) chain.
+
+enum { kReduceRedundant = 0, kReduceSliced = 1 };
+
+struct GlmLaunchShape {
+    int V;              // floats per vector load (1, 2, 4)
+    int CPL;            // vector chunks of a row held per lane
+    int PF;             // rows in flight per row slot
+    int L;              // lanes cooperating on one row (power of two <= 64)
+    int block;          // threads per workgroup
+    int G;              // workgroups
+    int reduce_mode;    // kReduce*
+    size_t lds_bytes;
+    int max_G;          // co-resident workgroups the device can hold for this kernel
+};
+
+struct GlmArgs {
+    const float* X;         // [rows][p]
+    const float* y;         // [rows]
+    const int32_t* perm;    // [npass][perm_stride]: partition of pass t at perm + t * perm_stride
+    float* theta;           // [p]
+    float* partial;         // [2][G][p] per-workgroup gradient sums, double buffered by step parity
+    unsigned* sync;         // [0] arrive counter, [1] abort flag
+    int rows, p, n, npass;
+    int perm_stride;        // rows, or 0 when every pass reuses one partition
+    int model;
+    int L, logL;
+    int reduce_mode;
+    float alpha;
+    long long timeout_ticks;
+    int single_step;        // >= 0: process only that step and stop after writing partial sums
+};
+
+// Pick V/CPL/PF/L/block/G/reduce mode for a shape; returns false if p is outside the supported range.
+bool glm_plan(int64_t p, int64_t n, int requested_G, int num_cus, GlmLaunchShape* out, char* why, size_t why_len);
+// Query co-residency and set attributes; fills shape->max_G and clamps shape->G.
+hipError_t glm_prepare(GlmLaunchShape* shape);
+// One cooperative launch covering npass passes over the buffer.
+hipError_t glm_launch_chain(const GlmLaunchShape& shape, const GlmArgs& args, hipStream_t stream);
+// Step-per-launch variant: partial sums for step `args.single_step`, then reduce + update.
+hipError_t glm_launch_step(const GlmLaunchShape& shape, const GlmArgs& args, int nb, hipStream_t stream);
+
+}  // namespace bmgd

@@ -1,0 +1,534 @@
+// Fused mini-batch gradient + update for least squares and logistic regression.
+//
+// One step of eq. (2.1): theta <- theta - alpha/n_b * sum_{i in batch} (b'(x_i'theta) - y_i) x_i, with
+// b' the identity (eq. (3.1)) or the sigmoid (Section 3.2.3).  The steps of a pass, and the passes of a
+// buffer, depend on each other through theta (Algorithm 1's inner loops), so the whole chain for one
+// buffer runs inside ONE cooperative kernel: workgroups stay resident, each mini-batch is spread over all
+// of them, and a grid-wide barrier per step stands where a kernel boundary would otherwise be.
+//
+// Data path of a step (per row, read from HBM exactly once):
+//   * a row is held in the registers of L cooperating lanes (L a power of two, 64/L rows per wavefront);
+//     lane l owns the columns V*(l + L*k) .. +V-1, k < CPL, and keeps its slice of theta and of the
+//     gradient accumulator for exactly those columns;
+//   * u = x'theta is finished with DPP / permlane-swap butterflies inside the wavefront, the residual
+//     is formed, and the same registers feed acc += r * x;
+//   * accumulators are summed over the row slots of a wavefront (lane shuffles), over wavefronts (LDS)
+//     and over workgroups (global partial sums, fixed order, so results are reproducible run to run);
+//   * rows of the next step do not depend on theta: their loads are issued before the barrier wait and
+//     are in flight while the barrier resolves.
+//
+// Reduction across workgroups, two forms:
+//   redundant  every workgroup sums all partials itself and keeps its own copy of theta (one barrier per
+//              step; for small p * G);
+//   sliced     workgroup g sums a slice of the columns, writes that slice of theta, second barrier, all
+//              re-read theta (for large p).
+#include "bmgd_internal.h"
+
+#include <stdio.h>
+
+#include <algorithm>
+
+namespace bmgd {
+
+namespace {
+
+enum { kLinear = 0, kLogistic = 1 };
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    return __builtin_bit_cast(float,
+                              __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// lane i of an even 16-lane row + lane i of the odd row next to it, result in both
+__device__ __forceinline__ float swap16_sum(float v)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, r[1]);
+}
+
+// lane i of the lower half-wave + lane i of the upper half-wave, result in both
+__device__ __forceinline__ float swap32_sum(float v)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, r[1]);
+}
+
+// Sum over each aligned group of L consecutive lanes; every lane of the group receives the sum.
+__device__ __forceinline__ float group_sum(float v, int L)
+{
+    if (L >= 2) v += dpp_mov<0xB1>(v);    // quad_perm [1,0,3,2]
+    if (L >= 4) v += dpp_mov<0x4E>(v);    // quad_perm [2,3,0,1]
+    if (L >= 8) v += dpp_mov<0x141>(v);   // row_half_mirror (both quads already hold their sums)
+    if (L >= 16) v += dpp_mov<0x140>(v);  // row_mirror
+    if (L >= 32) v = swap16_sum(v);
+    if (L >= 64) v = swap32_sum(v);
+    return v;
+}
+
+// Sum over the lanes that share lane % L (one per row slot of the wavefront); valid in lanes < L.
+__device__ __forceinline__ float slot_sum(float v, int L)
+{
+    if (L <= 1) v += dpp_mov<0x121>(v);   // row_ror 1
+    if (L <= 2) v += dpp_mov<0x122>(v);   // row_ror 2
+    if (L <= 4) v += dpp_mov<0x124>(v);   // row_ror 4
+    if (L <= 8) v += dpp_mov<0x128>(v);   // row_ror 8
+    if (L <= 16) v = swap16_sum(v);
+    if (L <= 32) v = swap32_sum(v);
+    return v;
+}
+
+template <int V>
+__device__ __forceinline__ void load_vec(const float* __restrict__ src, float* dst)
+{
+    if constexpr (V == 4) {
+        const float4 t = *reinterpret_cast<const float4*>(src);
+        dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w;
+    } else if constexpr (V == 2) {
+        const float2 t = *reinterpret_cast<const float2*>(src);
+        dst[0] = t.x; dst[1] = t.y;
+    } else {
+        dst[0] = *src;
+    }
+}
+
+__device__ __forceinline__ float residual(int model, float u, float y)
+{
+    if (model == kLogistic) {
+        const float e = expf(-fabsf(u));
+        const float s = (u >= 0.f) ? 1.f / (1.f + e) : e / (1.f + e);
+        return s - y;
+    }
+    return u - y;
+}
+
+// Grid-wide barrier on a monotonically increasing arrival counter.  Every wait is bounded: after
+// `timeout` ticks of the 100 MHz wall clock the abort flag is raised, which every other waiter sees.
+// Returns true when the kernel must exit.
+__device__ __forceinline__ void barrier_arrive(unsigned* sync)
+{
+    __hip_atomic_fetch_add(&sync[0], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ int barrier_wait(unsigned* sync, unsigned target, long long timeout)
+{
+    int aborted = 0;
+    const long long t0 = wall_clock64();
+    while (__hip_atomic_load(&sync[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        if (__hip_atomic_load(&sync[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+            aborted = 1;
+            break;
+        }
+        if (wall_clock64() - t0 > timeout) {
+            __hip_atomic_store(&sync[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            aborted = 1;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // pairs with the arrivals' release
+    return aborted;
+}
+
+template <int V, int CPL, int PF>
+struct RowGroup {
+    float x[PF][CPL * V];
+    float y[PF];
+};
+
+template <int V, int CPL, int PF, bool THL, bool DB, int BLOCK>
+__global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
+{
+    extern __shared__ __align__(16) float smem[];
+    __shared__ int s_abort;
+
+    constexpr int NW = BLOCK / 64;
+    constexpr int E = CPL * V;                       // floats of a row held per lane
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int L = a.L;
+    const int lsub = lane & (L - 1);
+    const int slot = lane >> a.logL;
+    const int rpw = 64 >> a.logL;                    // rows per wavefront
+    const int G = gridDim.x;
+    const int p = a.p;
+    const int S_total = G * NW * rpw;
+    const int myslot = (blockIdx.x * NW + wave) * rpw + slot;
+    const int th_len = max((p + 63) & ~63, V * L * CPL);
+    float* th_lds = smem;                            // [th_len]
+    float* wpart = smem + th_len;                    // [NW][p], later reused as reduction scratch
+    const int M = (a.rows + a.n - 1) / a.n;
+    const int first = a.single_step >= 0 ? a.single_step : 0;
+    const int last = a.single_step >= 0 ? a.single_step + 1 : a.npass * M;
+
+    int col[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) col[k] = V * (lsub + L * k);
+
+    for (int c = tid; c < th_len; c += BLOCK) th_lds[c] = c < p ? a.theta[c] : 0.f;
+    if (tid == 0) s_abort = 0;
+    __syncthreads();
+
+    float th[THL ? 1 : E];
+    auto load_theta_regs = [&]() {
+        if constexpr (!THL) {
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) load_vec<V>(th_lds + col[k], th + k * V);
+        }
+    };
+    load_theta_regs();
+
+    // Batch geometry of step s.
+    auto batch_rows = [&](int s) { const int m = s % M; return min(a.n, a.rows - m * a.n); };
+    auto batch_base = [&](int s) { return (s / M) * a.perm_stride + (s % M) * a.n; };
+    auto batch_iters = [&](int s) { return (batch_rows(s) + S_total * PF - 1) / (S_total * PF); };
+
+    // Row indices of group (s, it) for this lane's row slot; -1 where the slot has no row.
+    auto load_idx = [&](int s, int it, int (&idx)[PF]) {
+        if (s >= last) {
+#pragma unroll
+            for (int q = 0; q < PF; ++q) idx[q] = -1;
+            return;
+        }
+        const int nb = batch_rows(s), base = batch_base(s);
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int j = (it * PF + q) * S_total + myslot;
+            idx[q] = j < nb ? a.perm[base + j] : -1;
+        }
+    };
+    auto issue_rows = [&](const int (&idx)[PF], RowGroup<V, CPL, PF>& g) {
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const bool ok = idx[q] >= 0;
+            const float* row = a.X + (size_t)(ok ? idx[q] : 0) * p;
+            g.y[q] = ok ? a.y[idx[q]] : 0.f;
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) {
+                if (ok && col[k] < p) {
+                    load_vec<V>(row + col[k], &g.x[q][k * V]);
+                } else {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) g.x[q][k * V + v] = 0.f;
+                }
+            }
+        }
+    };
+
+    RowGroup<V, CPL, PF> cur, nxt;                   // nxt is only live when DB
+    int idxn[PF];
+    load_idx(first, 0, idxn);
+    issue_rows(idxn, cur);
+    {   // indices of the group after (first, 0)
+        const bool in_step = 1 < batch_iters(first);
+        load_idx(in_step ? first : first + 1, in_step ? 1 : 0, idxn);
+    }
+
+    unsigned arrivals = 0;                           // barrier generations completed by this grid
+    for (int s = first; s < last; ++s) {
+        const int nb = batch_rows(s);
+        const int iters = batch_iters(s);
+        float acc[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = 0.f;
+
+        for (int it = 0; it < iters; ++it) {
+            const bool more = it + 1 < iters;
+            const bool in_step = it + 2 < iters;
+            if constexpr (DB) {
+                if (more) {                          // rows of the next group fly while this one is used
+                    issue_rows(idxn, nxt);
+                    load_idx(in_step ? s : s + 1, in_step ? it + 2 : 0, idxn);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < PF; ++q) {
+                float dot = 0.f;
+#pragma unroll
+                for (int k = 0; k < CPL; ++k) {
+                    float t[V];
+                    if constexpr (THL) load_vec<V>(th_lds + col[k], t);
+#pragma unroll
+                    for (int v = 0; v < V; ++v)
+                        dot = fmaf(cur.x[q][k * V + v], THL ? t[v] : th[(THL ? 0 : k * V + v)], dot);
+                    if constexpr (THL) {             // keep theta reads from LDS from piling up in registers
+                        if ((k & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                dot = group_sum(dot, L);
+                const float r = residual(a.model, dot, cur.y[q]);   // rows without data have x = 0
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[e] = fmaf(r, cur.x[q][e], acc[e]);
+            }
+            if (more) {
+                if constexpr (DB) {
+                    cur = nxt;
+                } else {                             // wide rows: other wavefronts cover the latency
+                    issue_rows(idxn, cur);
+                    load_idx(in_step ? s : s + 1, in_step ? it + 2 : 0, idxn);
+                }
+            }
+        }
+
+        // wavefront partial: sum the row slots, lanes < L hold it
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = slot_sum(acc[e], L);
+        if (lane < L) {
+#pragma unroll
+            for (int k = 0; k < CPL; ++k)
+                if (col[k] < p) {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) wpart[wave * p + col[k] + v] = acc[k * V + v];
+                }
+        }
+        __syncthreads();
+
+        const float scale = a.alpha / (float)nb;
+        if (G == 1 && a.single_step < 0) {
+            // single workgroup: the workgroup sum is the batch sum
+            for (int c = tid; c < p; c += BLOCK) {
+                float t = 0.f;
+                for (int w = 0; w < NW; ++w) t += wpart[w * p + c];
+                th_lds[c] -= scale * t;
+            }
+            __syncthreads();
+            if (s + 1 < last) {
+                issue_rows(idxn, cur);
+                const bool in_step = 1 < batch_iters(s + 1);
+                load_idx(in_step ? s + 1 : s + 2, in_step ? 1 : 0, idxn);
+            }
+            load_theta_regs();
+            continue;
+        }
+
+        float* part = a.partial + (size_t)(s & 1) * G * p;
+        for (int c = tid; c < p; c += BLOCK) {
+            float t = 0.f;
+            for (int w = 0; w < NW; ++w) t += wpart[w * p + c];
+            part[(size_t)blockIdx.x * p + c] = t;
+        }
+        if (a.single_step >= 0) return;              // step-per-launch: a second kernel reduces and updates
+
+        __syncthreads();                             // all partial stores of this workgroup are issued
+        if (tid == 0) barrier_arrive(a.sync);
+        ++arrivals;
+        if (s + 1 < last) {                          // next step's rows: in flight while the barrier resolves
+            issue_rows(idxn, cur);
+            const bool in_step = 1 < batch_iters(s + 1);
+            load_idx(in_step ? s + 1 : s + 2, in_step ? 1 : 0, idxn);
+        }
+        if (tid == 0) s_abort = barrier_wait(a.sync, arrivals * (unsigned)G, a.timeout_ticks);
+        __syncthreads();
+        if (s_abort) return;
+
+        // sum partials over workgroups in fixed order and apply the update
+        int c_lo = 0, c_hi = p;
+        if (a.reduce_mode == kReduceSliced) {
+            const int cw = (p + G - 1) / G;
+            c_lo = min(p, (int)blockIdx.x * cw);
+            c_hi = min(p, c_lo + cw);
+        }
+        const int width = c_hi - c_lo;
+        if (width > 0) {
+            const int W = min(width, BLOCK);
+            const int NG = BLOCK / W;
+            const int cj = tid % W, gs = tid / W;
+            for (int cb = c_lo; cb < c_hi; cb += W) {
+                const int c = cb + cj;
+                if (gs < NG && c < c_hi) {
+                    float t = 0.f;
+#pragma unroll 8
+                    for (int g = gs; g < G; g += NG) t += part[(size_t)g * p + c];
+                    wpart[gs * W + cj] = t;
+                }
+                __syncthreads();
+                if (tid < W && cb + tid < c_hi) {
+                    float t = 0.f;
+                    for (int q = 0; q < NG; ++q) t += wpart[q * W + tid];
+                    const float v = th_lds[cb + tid] - scale * t;
+                    th_lds[cb + tid] = v;
+                    if (a.reduce_mode == kReduceSliced) a.theta[cb + tid] = v;
+                }
+                __syncthreads();
+            }
+        }
+        if (a.reduce_mode == kReduceSliced) {
+            __syncthreads();
+            if (tid == 0) barrier_arrive(a.sync);
+            ++arrivals;
+            if (tid == 0) s_abort = barrier_wait(a.sync, arrivals * (unsigned)G, a.timeout_ticks);
+            __syncthreads();
+            if (s_abort) return;
+            for (int c = tid; c < p; c += BLOCK) th_lds[c] = a.theta[c];
+            __syncthreads();
+        }
+        load_theta_regs();
+    }
+
+    if (a.reduce_mode == kReduceRedundant && blockIdx.x == 0 && a.single_step < 0) {
+        for (int c = tid; c < p; c += BLOCK) a.theta[c] = th_lds[c];
+    }
+}
+
+// Step-per-launch companion: theta[c] -= scale * sum_g partial[g][c], one thread per column.
+__global__ void __launch_bounds__(256) glm_update_kernel(float* __restrict__ theta, const float* __restrict__ part,
+                                                         int p, int G, float scale)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= p) return;
+    float t = 0.f;
+    for (int g = 0; g < G; ++g) t += part[(size_t)g * p + c];
+    theta[c] -= scale * t;
+}
+
+using KernelFn = void (*)(GlmArgs);
+
+// Rows in flight per slot are limited so that cur + next stay in registers: CPL * V * PF <= 16 floats.
+constexpr int max_pf_for(int v, int cpl)
+{
+    int pf = 16 / (v * cpl);
+    return pf < 1 ? 1 : pf > 8 ? 8 : pf;
+}
+
+template <int V, int CPL, int PF>
+KernelFn pick()
+{
+    if constexpr (PF > max_pf_for(V, CPL)) {
+        return nullptr;
+    } else {
+        constexpr bool wide = CPL >= 8;
+        return glm_chain_kernel<V, CPL, PF, wide, !wide, wide ? 512 : 1024>;
+    }
+}
+
+template <int V, int CPL>
+KernelFn pick_pf(int pf)
+{
+    switch (pf) {
+    case 1: return pick<V, CPL, 1>();
+    case 2: return pick<V, CPL, 2>();
+    case 4: return pick<V, CPL, 4>();
+    case 8: return pick<V, CPL, 8>();
+    }
+    return nullptr;
+}
+
+template <int V>
+KernelFn pick_v(int cpl, int pf)
+{
+    switch (cpl) {
+    case 1: return pick_pf<V, 1>(pf);
+    case 2: return pick_pf<V, 2>(pf);
+    case 4: return pick_pf<V, 4>(pf);
+    case 8: return pick_pf<V, 8>(pf);
+    case 16: return pick_pf<V, 16>(pf);
+    }
+    return nullptr;
+}
+
+KernelFn pick_kernel(const GlmLaunchShape& s)
+{
+    switch (s.V) {
+    case 1: return pick_v<1>(s.CPL, s.PF);
+    case 2: return pick_v<2>(s.CPL, s.PF);
+    case 4: return pick_v<4>(s.CPL, s.PF);
+    }
+    return nullptr;
+}
+
+
+}  // namespace
+
+bool glm_plan(int64_t p, int64_t n, int requested_G, int num_cus, GlmLaunchShape* out, char* why, size_t why_len)
+{
+    GlmLaunchShape s{};
+    s.V = (p % 4 == 0) ? 4 : (p % 2 == 0) ? 2 : 1;
+    const int64_t chunks = p / s.V;
+    if (chunks <= 64) {
+        s.L = 1;
+        while (s.L < chunks) s.L *= 2;
+        s.CPL = 1;
+    } else {
+        s.L = 64;
+        const int64_t need = (chunks + 63) / 64;
+        s.CPL = 1;
+        while (s.CPL < need) s.CPL *= 2;
+        if (s.CPL > 16) {
+            snprintf(why, why_len, "p = %lld is above the supported maximum (%d for this alignment of p)",
+                     (long long)p, 64 * 16 * s.V);
+            return false;
+        }
+    }
+    s.block = s.CPL >= 8 ? 512 : 1024;
+    const int slots_per_group = (s.block / 64) * (64 / s.L);
+    int G = requested_G;
+    if (G <= 0) {
+        const int64_t bytes = n * p * 4;
+        G = (int)((bytes + 32767) / 32768);
+    }
+    if (G < 1) G = 1;
+    if (G > num_cus) G = num_cus;
+    s.G = G;
+    s.PF = 1;
+    while (s.PF < max_pf_for(s.V, s.CPL) && (int64_t)G * slots_per_group * s.PF < n) s.PF *= 2;
+    s.reduce_mode = ((int64_t)G * p * 4 <= 256 * 1024) ? kReduceRedundant : kReduceSliced;
+    const int64_t th_len = std::max<int64_t>((p + 63) & ~int64_t(63), (int64_t)s.V * s.L * s.CPL);
+    s.lds_bytes = (size_t)(th_len + (int64_t)(s.block / 64) * p + 64) * sizeof(float);
+    if (s.lds_bytes < (size_t)(th_len + s.block + 64) * sizeof(float))
+        s.lds_bytes = (size_t)(th_len + s.block + 64) * sizeof(float);
+    *out = s;
+    return true;
+}
+
+hipError_t glm_prepare(GlmLaunchShape* s)
+{
+    KernelFn fn = pick_kernel(*s);
+    if (!fn) return hipErrorInvalidValue;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)s->lds_bytes);
+    if (e != hipSuccess) return e;
+    int per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(fn), s->block,
+                                                     s->lds_bytes);
+    if (e != hipSuccess) return e;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
+    s->max_G = per_cu * prop.multiProcessorCount;
+    if (s->max_G < 1) return hipErrorLaunchOutOfResources;
+    // one workgroup per compute unit at most: the barrier cost grows with the number of arrivals
+    if (s->G > prop.multiProcessorCount) s->G = prop.multiProcessorCount;
+    if (s->G > s->max_G) s->G = s->max_G;
+    return hipSuccess;
+}
+
+hipError_t glm_launch_chain(const GlmLaunchShape& s, const GlmArgs& args, hipStream_t stream)
+{
+    KernelFn fn = pick_kernel(s);
+    if (!fn || s.G < 1 || s.G > s.max_G) return hipErrorInvalidValue;
+    GlmArgs a = args;
+    a.single_step = -1;
+    void* params[] = {&a};
+    return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(fn), dim3(s.G), dim3(s.block), params,
+                                      (unsigned)s.lds_bytes, stream);
+}
+
+hipError_t glm_launch_step(const GlmLaunchShape& s, const GlmArgs& args, int nb, hipStream_t stream)
+{
+    KernelFn fn = pick_kernel(s);
+    if (!fn || s.G < 1 || args.single_step < 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fn, dim3(s.G), dim3(s.block), s.lds_bytes, stream, args);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const float* part = args.partial + (size_t)(args.single_step & 1) * s.G * args.p;
+    hipLaunchKernelGGL(glm_update_kernel, dim3((args.p + 255) / 256), dim3(256), 0, stream, args.theta, part,
+                       args.p, s.G, args.alpha / (float)nb);
+    return hipGetLastError();
+}
+
+}  // namespace bmgd

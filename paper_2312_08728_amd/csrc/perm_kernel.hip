@@ -1,0 +1,86 @@
+// Device-side seeded partition of a buffer into mini-batches.
+//
+// Algorithm 1 draws a fresh random partition of the buffer at the start of every pass; Section 2.2
+// asks for disjoint parts that cover the buffer.  The generator is a keyed 8-round balanced Feistel
+// network on 2h bits (2^(2h) < 4 * rows) restricted to [0, rows) by cycle walking, in uint32 arithmetic
+// only, so that the index arrays are reproducible bit for bit.  Mini-batch m is
+// perm[(m-1) n : min(m n, rows)).
+#include "bmgd_internal.h"
+
+namespace bmgd {
+
+namespace {
+
+__host__ __device__ inline uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7FEB352Du;
+    x ^= x >> 15;
+    x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+
+struct KeyRow {
+    uint32_t k[kPermRounds];
+};
+
+__device__ inline uint32_t feistel(uint32_t x, const KeyRow& key, uint32_t h, uint32_t mask)
+{
+    uint32_t left = x >> h, right = x & mask;
+#pragma unroll
+    for (int i = 0; i < kPermRounds; ++i) {
+        const uint32_t f = mix32(right ^ key.k[i]) & mask;
+        const uint32_t t = left ^ f;
+        left = right;
+        right = t;
+    }
+    return (left << h) | right;
+}
+
+__global__ void __launch_bounds__(256) perm_kernel(int32_t* __restrict__ out, uint32_t rows, uint32_t h,
+                                                   PermKeys keys)
+{
+    const uint32_t pass = blockIdx.y;
+    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= rows) return;
+    KeyRow key;
+#pragma unroll
+    for (int i = 0; i < kPermRounds; ++i) key.k[i] = keys.key[pass][i];
+    const uint32_t mask = (1u << h) - 1u;
+    // j < rows lies on a cycle of the bijection that returns to j, so the walk always re-enters [0, rows).
+    uint32_t x = feistel(j, key, h, mask);
+    while (x >= rows) x = feistel(x, key, h, mask);
+    out[(size_t)pass * rows + j] = (int32_t)x;
+}
+
+}  // namespace
+
+void perm_round_keys(uint64_t seed, uint32_t b, uint32_t t, uint32_t out[kPermRounds])
+{
+    uint32_t a = mix32((uint32_t)(seed & 0xFFFFFFFFu) ^ 0x9E3779B9u);
+    a = mix32(a ^ (uint32_t)(seed >> 32));
+    a = mix32(a + b);
+    a = mix32(a ^ t);
+    for (int i = 0; i < kPermRounds; ++i) out[i] = mix32(a + (uint32_t)i * 0x9E3779B9u);
+}
+
+int perm_half_width(int64_t rows)
+{
+    int bits = 0;
+    for (uint64_t v = (uint64_t)(rows - 1); v != 0; v >>= 1) ++bits;
+    const int h = (bits + 1) / 2;
+    return h < 1 ? 1 : h;
+}
+
+hipError_t launch_perm(int32_t* out, int64_t rows, int npass, const PermKeys& keys, hipStream_t stream)
+{
+    if (rows <= 0 || npass <= 0) return hipSuccess;
+    if (npass > kMaxPassesPerLaunch || rows > (int64_t(1) << 30)) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((rows + 255) / 256), (unsigned)npass);
+    hipLaunchKernelGGL(perm_kernel, grid, dim3(256), 0, stream, out, (uint32_t)rows,
+                       (uint32_t)perm_half_width(rows), keys);
+    return hipGetLastError();
+}
+
+}  // namespace bmgd

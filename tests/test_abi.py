@@ -1,0 +1,84 @@
+"""The C-ABI library loads, exports every function include/bmgd.h declares, and rejects bad arguments
+before touching a GPU.  No compute is attempted here."""
+import ctypes
+import os
+import re
+
+import paper_2312_08728_amd as B
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "bmgd.h")
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bmgd_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = _declared()
+    assert len(names) >= 15
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+        assert n in B.EXPORTS and callable(getattr(B, n)), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_struct_layouts_match_header_order():
+    text = open(HEADER).read()
+    body = re.search(r"typedef struct bmgd_config \{(.*?)\} bmgd_config;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b(\w+);", body)
+    assert fields == [f[0] for f in B.bmgd_config._fields_]
+    body = re.search(r"typedef struct bmgd_stats \{(.*?)\} bmgd_stats;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    assert re.findall(r"\b(\w+);", body) == [f[0] for f in B.bmgd_stats._fields_]
+
+
+def _cfg(**kw):
+    c = B.bmgd_default_config()
+    c.p, c.buffer_n, c.batch_n, c.lr, c.passes = 100, 1000, 100, 0.1, 2
+    for k, v in kw.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_defaults():
+    c = B.bmgd_default_config()
+    assert (c.model, c.n_classes, c.x_dtype, c.seed, c.reshuffle, c.chain, c.n_workgroups) == (0, 1, 0, 0, 0, 0, 0)
+    assert c.workspace is None and c.workspace_bytes == 0
+
+
+def test_workspace_size_needs_no_gpu_and_grows_with_the_buffer():
+    a = B.bmgd_workspace_bytes(_cfg())
+    b = B.bmgd_workspace_bytes(_cfg(buffer_n=2000))
+    assert a >= 2 * (1000 * 100 * 4 + 1000 * 4) and b > a + 2 * 1000 * 100 * 4 - 1
+    assert a % 256 == 0
+
+
+def test_invalid_arguments_are_rejected_without_a_device():
+    bad = [dict(p=0), dict(buffer_n=0), dict(buffer_n=1 << 30), dict(batch_n=0), dict(batch_n=1001),
+           dict(lr=0.0), dict(lr=float("nan")), dict(lr=float("inf")), dict(lr=-1.0), dict(passes=0),
+           dict(model=7), dict(x_dtype=1), dict(reshuffle=5), dict(chain=9), dict(n_workgroups=-1),
+           dict(n_workgroups=257), dict(p=4100), dict(p=2050), dict(p=1025), dict(workspace=8),
+           dict(model=2, n_classes=1, x_dtype=1), dict(model=2, n_classes=10, x_dtype=0)]
+    for kw in bad:
+        cfg = _cfg(**kw)
+        assert B.bmgd_workspace_bytes(cfg) == 0, kw
+        rc, h = B.bmgd_create_ex(cfg)
+        assert rc == B.BMGD_EINVAL and h is None, kw
+        assert B.bmgd_last_error(None) != ""
+    assert B.bmgd_create(0, 10, 10, 0.1, 1) is None
+    for fn in (B.bmgd_sync, B.bmgd_run_buffer):
+        assert fn(None) == B.BMGD_EINVAL
+    B.bmgd_destroy(None)                        # ignored
+
+
+def test_no_silent_cpu_path():
+    """Without a GPU, creating a context must fail with BMGD_EHIP rather than compute anywhere else."""
+    import torch
+    if torch.cuda.is_available():
+        return
+    rc, h = B.bmgd_create_ex(_cfg())
+    assert rc == B.BMGD_EHIP and h is None

@@ -1,0 +1,144 @@
+"""Parity of the HIP chain (least squares, logistic) with the fp64 oracle: final theta after whole runs,
+relative L2 error <= 1e-4 (fp32 arithmetic against fp64; the iteration is contractive, so per-step
+rounding of order 1e-7 does not accumulate beyond that)."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_util import gpu_run, oracle_run, rel_l2
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def _case(model, N, p, N0, n, T, R, alpha, **kw):
+    base = wl.CONFIGS["cfg3" if model == wl.LOGISTIC else "cfg2"]
+    return base.scaled(name="case", model=model, N=N, p=p, N0=N0, n=n, T=T, R=R, alpha=alpha, **kw)
+
+
+def test_cfg1_full_run():
+    w = wl.CONFIGS["cfg1"]
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y)
+    got, st = gpu_run(w, X, y)
+    assert st.steps == w.steps and st.sample_gradients == w.sample_gradients
+    assert st.h2d_bytes == w.R * (X.nbytes + y.nbytes)
+    assert rel_l2(got, want) <= TOL
+
+
+# p chosen to hit every vector width / lanes-per-row / chunks-per-lane combination, with ragged batches
+SHAPES = [
+    # model, p, N0, n
+    (wl.LINEAR, 1, 300, 64), (wl.LINEAR, 3, 1000, 96), (wl.LINEAR, 10, 2000, 100), (wl.LINEAR, 37, 3000, 500),
+    (wl.LOGISTIC, 64, 5000, 1000), (wl.LINEAR, 100, 10_000, 1000), (wl.LOGISTIC, 130, 6000, 1024),
+    (wl.LOGISTIC, 200, 30_000, 4096), (wl.LINEAR, 257, 3000, 700), (wl.LINEAR, 500, 10_000, 1000),
+    (wl.LOGISTIC, 1000, 5000, 2048), (wl.LINEAR, 1022, 3000, 1024), (wl.LINEAR, 2048, 5000, 2048),
+    (wl.LOGISTIC, 4096, 9000, 4096),
+]
+
+
+@pytest.mark.parametrize("model,p,N0,n", SHAPES)
+def test_shapes_two_buffers(model, p, N0, n):
+    N = 2 * N0 - 123                                    # second buffer is shorter than the first
+    w = _case(model, N, p, N0, n, T=2, R=2, alpha=0.5 / (p + 10) if model == wl.LINEAR else 0.1,
+              x_cov="identity")
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y)
+    got, st = gpu_run(w, X, y)
+    assert st.steps == w.steps
+    assert rel_l2(got, want) <= TOL, (st.n_workgroups, st.threads_per_group)
+
+
+@pytest.mark.parametrize("G", [1, 2, 7, 64, 256])
+@pytest.mark.parametrize("chain", [1, 2])
+def test_workgroup_counts_and_chain_modes(G, chain):
+    w = _case(wl.LOGISTIC, 12_000, 200, 6000, 1000, T=2, R=1, alpha=0.1)
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y)
+    got, st = gpu_run(w, X, y, n_workgroups=G, chain=chain)
+    assert st.n_workgroups == G and st.chain == chain
+    assert rel_l2(got, want) <= TOL
+
+
+def test_sliced_reduction_small_grid():
+    w = _case(wl.LINEAR, 6000, 4096, 3000, 1024, T=1, R=1, alpha=1e-4, x_cov="identity")
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y)
+    for G in (48, 256):
+        got, st = gpu_run(w, X, y, n_workgroups=G)
+        assert rel_l2(got, want) <= TOL, G
+
+
+def test_edge_cases():
+    for N, N0, n in [(1, 1, 1), (5, 5, 8), (64, 64, 64), (65, 64, 64), (1000, 1000, 1000), (999, 500, 1)]:
+        w = _case(wl.LINEAR, N, 6, N0, min(n, N0), T=3, R=2, alpha=0.05, x_cov="identity")
+        X, y = wl.dataset(w)
+        want = oracle_run(w, X, y)
+        got, _ = gpu_run(w, X, y)
+        assert rel_l2(got, want) <= TOL, (N, N0, n)
+
+
+def test_resident_path_equals_loader_path_bitwise_and_is_reproducible():
+    w = _case(wl.LOGISTIC, 20_000, 200, 8000, 1000, T=2, R=2, alpha=0.1)
+    X, y = wl.dataset(w)
+    a, _ = gpu_run(w, X, y)
+    b, _ = gpu_run(w, X, y)
+    c, _ = gpu_run(w, X, y, resident=True)
+    assert np.array_equal(a, b) and np.array_equal(a, c)
+
+
+def test_fixed_partition_mode():
+    from oracle import bmgd as O
+    w = _case(wl.LINEAR, 3000, 20, 1000, 100, T=3, R=3, alpha=0.02)
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y, reshuffle=O.FIXED)
+    got, _ = gpu_run(w, X, y, reshuffle=1)
+    assert rel_l2(got, want) <= TOL
+
+
+def test_initial_value_and_resume():
+    import paper_2312_08728_amd as B
+    w = _case(wl.LINEAR, 4000, 30, 1000, 100, T=2, R=1, alpha=0.02)
+    X, y = wl.dataset(w)
+    th0 = np.linspace(-1, 1, w.p).astype(np.float32)
+    want = oracle_run(w, X, y, theta0=th0)
+    got, _ = gpu_run(w, X, y, theta0=th0)
+    assert rel_l2(got, want) <= TOL
+    # stop after two buffers, carry (theta, buffer counter) into a new context, finish there
+    import torch
+    s = torch.cuda.Stream()
+    xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    c1 = B.Context(w.p, w.N0, w.n, w.alpha, w.T)
+    c1.set_theta(th0)
+    for k in range(2):
+        c1.run_device_buffer(xd[k * 1000:(k + 1) * 1000], yd[k * 1000:(k + 1) * 1000], 1000, s)
+    mid = c1.get_theta()
+    c1.close()
+    c2 = B.Context(w.p, w.N0, w.n, w.alpha, w.T)
+    c2.set_theta(mid)
+    c2.set_position(2)
+    for k in range(2, 4):
+        c2.run_device_buffer(xd[k * 1000:(k + 1) * 1000], yd[k * 1000:(k + 1) * 1000], 1000, s)
+    fin = c2.get_theta()
+    c2.close()
+    assert np.array_equal(fin, got)
+
+
+def test_error_paths():
+    import torch
+    import paper_2312_08728_amd as B
+    c = B.Context(8, 100, 10, 0.1, 1)
+    x = torch.zeros(100, 8).pin_memory()
+    y = torch.zeros(100).pin_memory()
+    assert B.bmgd_run_buffer(c.h, None) == B.BMGD_ESTATE
+    assert B.bmgd_load_buffer_async(c.h, x, y, 101, None) == B.BMGD_EINVAL
+    assert B.bmgd_load_buffer_async(c.h, x, y, 0, None) == B.BMGD_EINVAL
+    assert B.bmgd_load_buffer_async(c.h, None, y, 10, None) == B.BMGD_EINVAL
+    assert B.bmgd_load_buffer_async(c.h, x, y, 100, None) == B.BMGD_OK
+    assert B.bmgd_load_buffer_async(c.h, x, y, 100, None) == B.BMGD_ESTATE
+    assert "already loaded" in B.bmgd_last_error(c.h)
+    assert B.bmgd_run_buffer(c.h, None) == B.BMGD_OK
+    out = np.zeros(9, dtype=np.float32)
+    assert B.bmgd_get_theta(c.h, out, 9) == B.BMGD_EINVAL
+    assert B.bmgd_get_theta(c.h, out, 8) == B.BMGD_OK
+    c.close()
