@@ -54,6 +54,10 @@ def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2312_08728_amd.build "
                           f"or __graft_entry__.build()); there is no fallback path")
+    # PyTorch bundles its own HIP runtime under the same soname as the system one; a process must use
+    # exactly one of them.  Importing torch first makes libbmgd bind to the runtime torch's allocator
+    # and streams already use.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int
     lib.bmgd_default_config.argtypes, lib.bmgd_default_config.restype = [C.POINTER(bmgd_config)], None

@@ -44,17 +44,23 @@ __device__ __forceinline__ float dpp_mov(float v)
 // lane i of an even 16-lane row + lane i of the odd row next to it, result in both
 __device__ __forceinline__ float swap16_sum(float v)
 {
-    const unsigned u = __builtin_bit_cast(unsigned, v);
-    auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    return __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, r[1]);
+    // Both registers are rewritten by the instruction, so it is issued as inline assembly with two
+    // read-write operands (the compiler builtin hands back only one of the two results).  The s_nop
+    // covers the wait states the instruction needs after a VALU write of its operands.
+    float a = v, b = v;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+    return a + b;
 }
 
 // lane i of the lower half-wave + lane i of the upper half-wave, result in both
 __device__ __forceinline__ float swap32_sum(float v)
 {
-    const unsigned u = __builtin_bit_cast(unsigned, v);
-    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, r[1]);
+    // Both registers are rewritten by the instruction, so it is issued as inline assembly with two
+    // read-write operands (the compiler builtin hands back only one of the two results).  The s_nop
+    // covers the wait states the instruction needs after a VALU write of its operands.
+    float a = v, b = v;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+    return a + b;
 }
 
 // Sum over each aligned group of L consecutive lanes; every lane of the group receives the sum.
