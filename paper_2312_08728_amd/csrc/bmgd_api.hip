@@ -24,7 +24,7 @@ constexpr int kMaxGroups = 256;                    // upper bound used to size t
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t slot_x[2], slot_y[2], perm, theta, partial, sync, aux, total;
+    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, aux, total;
 };
 
 struct Slot {
@@ -58,7 +58,10 @@ struct bmgd_ctx {
     int32_t* perm = nullptr;
     float* theta = nullptr;
     float* partial = nullptr;
+    unsigned long long* ll_part = nullptr;
+    unsigned long long* ll_theta = nullptr;
     unsigned* sync = nullptr;
+    uint32_t tag_epoch = 0;                        // tags handed out so far for flagged-word exchanges
     GlmLaunchShape shape{};
     int chain = BMGD_CHAIN_PERSISTENT;
     int64_t buffer_counter = 0;
@@ -124,6 +127,9 @@ Layout make_layout(const bmgd_config& c)
     l.perm = off;    off += align_up((size_t)np * c.buffer_n * 4);
     l.theta = off;   off += align_up((size_t)c.p * C * 4);
     l.partial = off; off += align_up((size_t)2 * kMaxGroups * c.p * 4);
+    const size_t pp = ((size_t)c.p + 15) & ~size_t(15);   // flagged-word rows are padded to whole 128-byte lines
+    l.ll_part = off; off += align_up((size_t)2 * kMaxGroups * pp * 8);
+    l.ll_theta = off; off += align_up((size_t)2 * kThetaCopies * pp * 8);
     l.sync = off;    off += align_up(64);
     l.aux = off;
     l.total = off;
@@ -235,10 +241,18 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         a.alpha = (float)c.lr;
         a.timeout_ticks = ticks;
         a.single_step = -1;
-        if ((double)np * (double)M * 2.0 * ctx->shape.G > 4.0e9)
-            return fail(ctx, BMGD_EINVAL, "too many steps per launch for the barrier counter");
+        a.ll_part = ctx->ll_part;
+        a.ll_theta = ctx->ll_theta;
         if (ctx->chain == BMGD_CHAIN_PERSISTENT) {
-            HIP_TRY(ctx, hipMemsetAsync(ctx->sync, 0, sizeof(unsigned), stream));
+            const int64_t nsteps = (int64_t)np * M;
+            if (nsteps >= 0x7FFFFFFFLL) return fail(ctx, BMGD_EINVAL, "too many steps in one launch");
+            if ((uint64_t)ctx->tag_epoch + (uint64_t)nsteps + 1 >= 0xFFFFFFFFull) {
+                // tag space used up: clear the flagged words (stream-ordered) and start over
+                HIP_TRY(ctx, launch_fill_zero(ctx->ll_part, ctx->lay.sync - ctx->lay.ll_part, stream));
+                ctx->tag_epoch = 0;
+            }
+            a.tag_base = ctx->tag_epoch;
+            ctx->tag_epoch += (uint32_t)nsteps;
             HIP_TRY(ctx, glm_launch_chain(ctx->shape, a, stream));
         } else {
             for (int64_t s = 0; s < (int64_t)np * M; ++s) {
@@ -355,9 +369,13 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->perm = reinterpret_cast<int32_t*>(base + ctx->lay.perm);
     ctx->theta = reinterpret_cast<float*>(base + ctx->lay.theta);
     ctx->partial = reinterpret_cast<float*>(base + ctx->lay.partial);
+    ctx->ll_part = reinterpret_cast<unsigned long long*>(base + ctx->lay.ll_part);
+    ctx->ll_theta = reinterpret_cast<unsigned long long*>(base + ctx->lay.ll_theta);
     ctx->sync = reinterpret_cast<unsigned*>(base + ctx->lay.sync);
     CREATE_TRY(hipMemset(ctx->theta, 0, (size_t)ctx->theta_len * 4));
     CREATE_TRY(hipMemset(ctx->sync, 0, 64));
+    // flagged words start with tag 0, which no step ever waits for
+    CREATE_TRY(hipMemset(ctx->ll_part, 0, ctx->lay.sync - ctx->lay.ll_part));
     CREATE_TRY(hipEventCreate(&ctx->base));
     CREATE_TRY(hipEventRecord(ctx->base, nullptr));
 

@@ -9,6 +9,7 @@ namespace bmgd {
 
 constexpr int kPermRounds = 8;
 constexpr int kMaxPassesPerLaunch = 4;     // partitions kept on the device at a time
+constexpr int kThetaCopies = 8;            // copies of the theta broadcast (sliced reduction)
 
 // Round keys of the partition generator for up to kMaxPassesPerLaunch passes.
 struct PermKeys {
@@ -23,6 +24,9 @@ int perm_half_width(int64_t rows);
 // Device: out[pass][j] = PERM(...)[j] for j < rows, pass < npass (row stride = rows).
 hipError_t launch_perm(int32_t* out, int64_t rows, int npass, const PermKeys& keys, hipStream_t stream);
 
+// Device: zero `bytes` bytes at dst (both multiples of 16) with a kernel, in stream order.
+hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t stream);
+
 // ---------------------------------------------------------------------------------------------------
 // GLM (least squares / logistic) chain.
 
@@ -32,6 +36,7 @@ struct GlmLaunchShape {
     int V;              // floats per vector load (1, 2, 4)
     int CPL;            // vector chunks of a row held per lane
     int PF;             // rows in flight per row slot
+    int DB;             // 1: look-ahead of one row group inside a step
     int L;              // lanes cooperating on one row (power of two <= 64)
     int block;          // threads per workgroup
     int G;              // workgroups
@@ -45,8 +50,11 @@ struct GlmArgs {
     const float* y;         // [rows]
     const int32_t* perm;    // [npass][perm_stride]: partition of pass t at perm + t * perm_stride
     float* theta;           // [p]
-    float* partial;         // [2][G][p] per-workgroup gradient sums, double buffered by step parity
-    unsigned* sync;         // [0] arrive counter, [1] abort flag
+    float* partial;         // [2][G][p] per-workgroup gradient sums (step-per-launch mode)
+    unsigned long long* ll_part;   // [2][G][p] the same sums as flagged words {tag : float}, by step parity
+    unsigned long long* ll_theta;  // [2][kThetaCopies][p] updated theta as flagged words (sliced reduction)
+    unsigned* sync;         // [1] abort flag ([0] unused)
+    unsigned tag_base;      // tag of step s is tag_base + s + 1
     int rows, p, n, npass;
     int perm_stride;        // rows, or 0 when every pass reuses one partition
     int model;

@@ -111,33 +111,61 @@ __device__ __forceinline__ float residual(int model, float u, float y)
     return u - y;
 }
 
-// Grid-wide barrier on a monotonically increasing arrival counter.  Every wait is bounded: after
-// `timeout` ticks of the 100 MHz wall clock the abort flag is raised, which every other waiter sees.
-// Returns true when the kernel must exit.
-__device__ __forceinline__ void barrier_arrive(unsigned* sync)
+// Exchange between workgroups: "flagged words".  A value travels as one 64-bit word {tag : float bits}
+// written with a single 8-byte store; a reader polls the word until it carries the tag of the step it
+// waits for.  Data and readiness arrive together, so a step needs no separate barrier, fence or counter.
+// Tags grow monotonically over the life of a context and 0 is never used, hence stale words never match.
+__device__ __forceinline__ void ll_store(unsigned long long* dst, float v, unsigned tag)
 {
-    __hip_atomic_fetch_add(&sync[0], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long w = ((unsigned long long)tag << 32) | (unsigned long long)__builtin_bit_cast(unsigned, v);
+    __hip_atomic_store(dst, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ int barrier_wait(unsigned* sync, unsigned target, long long timeout)
+__device__ __forceinline__ unsigned long long ll_load(const unsigned long long* src)
 {
-    int aborted = 0;
-    const long long t0 = wall_clock64();
-    while (__hip_atomic_load(&sync[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-        if (__hip_atomic_load(&sync[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
-            aborted = 1;
-            break;
-        }
-        if (wall_clock64() - t0 > timeout) {
-            __hip_atomic_store(&sync[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            aborted = 1;
-            break;
-        }
-        __builtin_amdgcn_s_sleep(1);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // pairs with the arrivals' release
-    return aborted;
+    return __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+
+// Four flagged words requested back to back and awaited together.  (Written as inline assembly because
+// the compiler waits for each atomic load before issuing the next; the instruction is the one it emits
+// for an agent-scope load.)  The wait also covers this wavefront's older loads.
+__device__ __forceinline__ void ll_load4(const unsigned long long* const (&src)[4], unsigned long long (&w)[4])
+{
+    asm volatile("global_load_dwordx2 %0, %4, off sc1\n\t"
+                 "global_load_dwordx2 %1, %5, off sc1\n\t"
+                 "global_load_dwordx2 %2, %6, off sc1\n\t"
+                 "global_load_dwordx2 %3, %7, off sc1\n\t"
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]), "=&v"(w[3])
+                 : "v"(src[0]), "v"(src[1]), "v"(src[2]), "v"(src[3])
+                 : "memory");
+}
+
+// Every wait is bounded: a poll that has failed for `timeout` ticks of the 100 MHz wall clock raises the
+// abort flag, which every other poller checks, and the kernel exits.
+struct PollGuard {
+    unsigned* flag;
+    long long timeout;
+    long long t0;
+    unsigned misses;
+    // Called after a failed poll: backs off briefly (polls travel over the fabric; a storm of them slows
+    // the very stores they wait for), and reports true when the wait must be given up.
+    __device__ __forceinline__ bool expired()
+    {
+        __builtin_amdgcn_s_sleep(2);
+        ++misses;
+        if ((misses & 31u) != 0u) return false;
+        if (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return true;
+        const long long now = wall_clock64();
+        if (t0 == 0) t0 = now;
+        if (now - t0 > timeout) {
+            __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return true;
+        }
+        return false;
+    }
+    __device__ __forceinline__ void arm() { t0 = 0; misses = 0; }
+};
 
 template <int V, int CPL, int PF>
 struct RowGroup {
@@ -153,6 +181,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
 
     constexpr int NW = BLOCK / 64;
     constexpr int E = CPL * V;                       // floats of a row held per lane
+    constexpr int U = 4;                             // flagged words polled together by one thread
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -164,6 +193,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
     const int p = a.p;
     const int S_total = G * NW * rpw;
     const int myslot = (blockIdx.x * NW + wave) * rpw + slot;
+    const int pp = (p + 15) & ~15;                   // stride of flagged-word rows: writers own whole 128-byte lines
     const int th_len = max((p + 63) & ~63, V * L * CPL);
     float* th_lds = smem;                            // [th_len]
     float* wpart = smem + th_len;                    // [NW][p], later reused as reduction scratch
@@ -224,20 +254,79 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
             }
         }
     };
+    // Group (s, 0) into `g`, and the indices of the group that follows it into `idx`.
+    auto prefetch_step = [&](int s, RowGroup<V, CPL, PF>& g, int (&idx)[PF]) {
+        issue_rows(idx, g);
+        const bool in_step = 1 < batch_iters(s);
+        load_idx(in_step ? s : s + 1, in_step ? 1 : 0, idx);
+    };
 
     RowGroup<V, CPL, PF> cur, nxt;                   // nxt is only live when DB
     int idxn[PF];
     load_idx(first, 0, idxn);
-    issue_rows(idxn, cur);
-    {   // indices of the group after (first, 0)
-        const bool in_step = 1 < batch_iters(first);
-        load_idx(in_step ? first : first + 1, in_step ? 1 : 0, idxn);
-    }
+    prefetch_step(first, cur, idxn);
 
-    unsigned arrivals = 0;                           // barrier generations completed by this grid
+    PollGuard guard{a.sync + 1, a.timeout_ticks, 0, 0};
+
+    // Sum over workgroups, in fixed order, of the flagged words of columns [c_lo, c_hi) for `tag`; then
+    // `apply(c, sum)` runs once per column.  Leaves s_abort set if a wait ran out.
+    // Thread (gs, cj) fetches column c_lo + cj of workgroups gs, gs + NG, ...: U words are requested back to
+    // back and awaited together, so a thread pays one trip over the fabric per U workgroups.
+    auto gather_columns = [&](const unsigned long long* words, int c_lo, int c_hi, unsigned tag, auto&& apply) {
+        const int width = c_hi - c_lo;
+        if (width <= 0) return;
+        const int W = min(width, BLOCK);
+        const int NG = min(BLOCK / W, G);            // groups that have a workgroup to fetch
+        const int cj = tid % W, gs = tid / W;
+        for (int cb = c_lo; cb < c_hi; cb += W) {
+            const int c = cb + cj;
+            if (gs < NG && c < c_hi) {
+                float t = 0.f;
+                bool dead = false;
+                for (int g0 = gs; g0 < G && !dead; g0 += NG * U) {
+                    const unsigned long long* src[U];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) src[u] = words + (size_t)min(g0 + u * NG, G - 1) * pp + c;
+                    unsigned long long w[U];
+                    for (;;) {
+                        ll_load4(src, w);
+                        bool ready = true;
+#pragma unroll
+                        for (int u = 0; u < U; ++u)
+                            ready = ready && ((unsigned)(w[u] >> 32) == tag || g0 + u * NG >= G);
+                        if (ready) break;
+                        if (guard.expired()) { dead = true; break; }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (g0 + u * NG < G) t += __builtin_bit_cast(float, (unsigned)w[u]);
+                }
+                if (dead) s_abort = 1;
+                wpart[gs * W + cj] = t;
+            }
+            __syncthreads();
+            if (s_abort) return;
+            if (tid < W && cb + tid < c_hi) {
+                float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;   // fixed association, four loads in flight
+                int q = 0;
+                for (; q + 4 <= NG; q += 4) {
+                    t0 += wpart[q * W + tid];
+                    t1 += wpart[(q + 1) * W + tid];
+                    t2 += wpart[(q + 2) * W + tid];
+                    t3 += wpart[(q + 3) * W + tid];
+                }
+                for (; q < NG; ++q) t0 += wpart[q * W + tid];
+                apply(cb + tid, (t0 + t1) + (t2 + t3));
+            }
+            __syncthreads();
+        }
+    };
+
     for (int s = first; s < last; ++s) {
         const int nb = batch_rows(s);
         const int iters = batch_iters(s);
+        const unsigned tag = a.tag_base + (unsigned)s + 1u;
+        guard.arm();
         float acc[E];
 #pragma unroll
         for (int e = 0; e < E; ++e) acc[e] = 0.f;
@@ -273,7 +362,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
             if (more) {
                 if constexpr (DB) {
                     cur = nxt;
-                } else {                             // wide rows: other wavefronts cover the latency
+                } else {                             // other wavefronts cover the latency
                     issue_rows(idxn, cur);
                     load_idx(in_step ? s : s + 1, in_step ? it + 2 : 0, idxn);
                 }
@@ -294,7 +383,17 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
         __syncthreads();
 
         const float scale = a.alpha / (float)nb;
-        if (G == 1 && a.single_step < 0) {
+        if (a.single_step >= 0) {
+            // step-per-launch: plain partial sums, a second kernel reduces and updates
+            float* part = a.partial + (size_t)(s & 1) * G * p;
+            for (int c = tid; c < p; c += BLOCK) {
+                float t = 0.f;
+                for (int w = 0; w < NW; ++w) t += wpart[w * p + c];
+                part[(size_t)blockIdx.x * p + c] = t;
+            }
+            return;
+        }
+        if (G == 1) {
             // single workgroup: the workgroup sum is the batch sum
             for (int c = tid; c < p; c += BLOCK) {
                 float t = 0.f;
@@ -302,80 +401,58 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
                 th_lds[c] -= scale * t;
             }
             __syncthreads();
-            if (s + 1 < last) {
-                issue_rows(idxn, cur);
-                const bool in_step = 1 < batch_iters(s + 1);
-                load_idx(in_step ? s + 1 : s + 2, in_step ? 1 : 0, idxn);
-            }
+            if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
             load_theta_regs();
             continue;
         }
 
-        float* part = a.partial + (size_t)(s & 1) * G * p;
+        // publish this workgroup's sums as flagged words
+        unsigned long long* words = a.ll_part + (size_t)(s & 1) * G * pp;
         for (int c = tid; c < p; c += BLOCK) {
             float t = 0.f;
             for (int w = 0; w < NW; ++w) t += wpart[w * p + c];
-            part[(size_t)blockIdx.x * p + c] = t;
+            ll_store(words + (size_t)blockIdx.x * pp + c, t, tag);
         }
-        if (a.single_step >= 0) return;              // step-per-launch: a second kernel reduces and updates
+        // next step's rows do not depend on theta: in flight while the exchange resolves
+        if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
+        __syncthreads();                             // wpart is reused as scratch below
 
-        __syncthreads();                             // all partial stores of this workgroup are issued
-        if (tid == 0) barrier_arrive(a.sync);
-        ++arrivals;
-        if (s + 1 < last) {                          // next step's rows: in flight while the barrier resolves
-            issue_rows(idxn, cur);
-            const bool in_step = 1 < batch_iters(s + 1);
-            load_idx(in_step ? s + 1 : s + 2, in_step ? 1 : 0, idxn);
-        }
-        if (tid == 0) s_abort = barrier_wait(a.sync, arrivals * (unsigned)G, a.timeout_ticks);
-        __syncthreads();
-        if (s_abort) return;
-
-        // sum partials over workgroups in fixed order and apply the update
-        int c_lo = 0, c_hi = p;
-        if (a.reduce_mode == kReduceSliced) {
-            const int cw = (p + G - 1) / G;
-            c_lo = min(p, (int)blockIdx.x * cw);
-            c_hi = min(p, c_lo + cw);
-        }
-        const int width = c_hi - c_lo;
-        if (width > 0) {
-            const int W = min(width, BLOCK);
-            const int NG = BLOCK / W;
-            const int cj = tid % W, gs = tid / W;
-            for (int cb = c_lo; cb < c_hi; cb += W) {
-                const int c = cb + cj;
-                if (gs < NG && c < c_hi) {
-                    float t = 0.f;
-#pragma unroll 8
-                    for (int g = gs; g < G; g += NG) t += part[(size_t)g * p + c];
-                    wpart[gs * W + cj] = t;
-                }
-                __syncthreads();
-                if (tid < W && cb + tid < c_hi) {
-                    float t = 0.f;
-                    for (int q = 0; q < NG; ++q) t += wpart[q * W + tid];
-                    const float v = th_lds[cb + tid] - scale * t;
-                    th_lds[cb + tid] = v;
-                    if (a.reduce_mode == kReduceSliced) a.theta[cb + tid] = v;
-                }
-                __syncthreads();
-            }
-        }
-        if (a.reduce_mode == kReduceSliced) {
-            __syncthreads();
-            if (tid == 0) barrier_arrive(a.sync);
-            ++arrivals;
-            if (tid == 0) s_abort = barrier_wait(a.sync, arrivals * (unsigned)G, a.timeout_ticks);
+        if (a.reduce_mode == kReduceRedundant) {
+            gather_columns(words, 0, p, tag, [&](int c, float t) { th_lds[c] -= scale * t; });
+            if (s_abort) return;
+        } else {
+            const int cw = ((p + G - 1) / G + 15) & ~15;   // slices are whole lines of 16 words
+            const int c_lo = min(p, (int)blockIdx.x * cw), c_hi = min(p, c_lo + cw);
+            // The updated slice goes out in kThetaCopies copies; a workgroup polls copy (its index mod
+            // kThetaCopies), so no single set of words is polled by the whole grid.
+            unsigned long long* thw = a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp;
+            gather_columns(words, c_lo, c_hi, tag, [&](int c, float t) {
+                const float v = th_lds[c] - scale * t;
+#pragma unroll
+                for (int r = 0; r < kThetaCopies; ++r) ll_store(thw + (size_t)r * pp + c, v, tag);
+            });
             __syncthreads();
             if (s_abort) return;
-            for (int c = tid; c < p; c += BLOCK) th_lds[c] = a.theta[c];
+            const unsigned long long* mine = thw + (size_t)(blockIdx.x % kThetaCopies) * pp;
+            bool dead = false;
+            for (int c = tid; c < p; c += BLOCK) {
+                unsigned long long w;
+                for (;;) {
+                    w = ll_load(mine + c);
+                    if ((unsigned)(w >> 32) == tag) break;
+                    if (guard.expired()) { dead = true; break; }
+                }
+                if (dead) break;
+                th_lds[c] = __builtin_bit_cast(float, (unsigned)w);
+            }
+            if (dead) s_abort = 1;
             __syncthreads();
+            if (s_abort) return;
         }
         load_theta_regs();
     }
 
-    if (a.reduce_mode == kReduceRedundant && blockIdx.x == 0 && a.single_step < 0) {
+    if (blockIdx.x == 0 && a.single_step < 0) {
         for (int c = tid; c < p; c += BLOCK) a.theta[c] = th_lds[c];
     }
 }
@@ -393,45 +470,54 @@ __global__ void __launch_bounds__(256) glm_update_kernel(float* __restrict__ the
 
 using KernelFn = void (*)(GlmArgs);
 
-// Rows in flight per slot are limited so that cur + next stay in registers: CPL * V * PF <= 16 floats.
-constexpr int max_pf_for(int v, int cpl)
+// Rows in flight per row slot are limited by registers: CPL * V * PF <= 16 floats per group (two groups
+// are live with look-ahead inside a step, DB), at most 4 rows with look-ahead; wide rows hold one row.
+constexpr bool shape_ok(int v, int cpl, int pf, bool db)
 {
-    int pf = 16 / (v * cpl);
-    return pf < 1 ? 1 : pf > 8 ? 8 : pf;
+    const int e = v * cpl;
+    if (cpl >= 8) return pf == 1 && !db;
+    return e * pf <= 16 && (!db || pf <= 4);
 }
 
-template <int V, int CPL, int PF>
+int max_pf(int v, int cpl, bool db)
+{
+    int pf = 1;
+    while (pf < 8 && shape_ok(v, cpl, pf * 2, db)) pf *= 2;
+    return pf;
+}
+
+template <int V, int CPL, int PF, bool DB>
 KernelFn pick()
 {
-    if constexpr (PF > max_pf_for(V, CPL)) {
+    if constexpr (!shape_ok(V, CPL, PF, DB)) {
         return nullptr;
     } else {
         constexpr bool wide = CPL >= 8;
-        return glm_chain_kernel<V, CPL, PF, wide, !wide, wide ? 512 : 1024>;
+        return glm_chain_kernel<V, CPL, PF, wide, DB, wide ? 512 : 1024>;
     }
 }
 
 template <int V, int CPL>
-KernelFn pick_pf(int pf)
+KernelFn pick_pf(int pf, bool db)
 {
     switch (pf) {
-    case 1: return pick<V, CPL, 1>();
-    case 2: return pick<V, CPL, 2>();
-    case 4: return pick<V, CPL, 4>();
-    case 8: return pick<V, CPL, 8>();
+    case 1: return db ? pick<V, CPL, 1, true>() : pick<V, CPL, 1, false>();
+    case 2: return db ? pick<V, CPL, 2, true>() : pick<V, CPL, 2, false>();
+    case 4: return db ? pick<V, CPL, 4, true>() : pick<V, CPL, 4, false>();
+    case 8: return db ? pick<V, CPL, 8, true>() : pick<V, CPL, 8, false>();
     }
     return nullptr;
 }
 
 template <int V>
-KernelFn pick_v(int cpl, int pf)
+KernelFn pick_v(int cpl, int pf, bool db)
 {
     switch (cpl) {
-    case 1: return pick_pf<V, 1>(pf);
-    case 2: return pick_pf<V, 2>(pf);
-    case 4: return pick_pf<V, 4>(pf);
-    case 8: return pick_pf<V, 8>(pf);
-    case 16: return pick_pf<V, 16>(pf);
+    case 1: return pick_pf<V, 1>(pf, db);
+    case 2: return pick_pf<V, 2>(pf, db);
+    case 4: return pick_pf<V, 4>(pf, db);
+    case 8: return pick_pf<V, 8>(pf, db);
+    case 16: return pick_pf<V, 16>(pf, db);
     }
     return nullptr;
 }
@@ -439,9 +525,9 @@ KernelFn pick_v(int cpl, int pf)
 KernelFn pick_kernel(const GlmLaunchShape& s)
 {
     switch (s.V) {
-    case 1: return pick_v<1>(s.CPL, s.PF);
-    case 2: return pick_v<2>(s.CPL, s.PF);
-    case 4: return pick_v<4>(s.CPL, s.PF);
+    case 1: return pick_v<1>(s.CPL, s.PF, s.DB != 0);
+    case 2: return pick_v<2>(s.CPL, s.PF, s.DB != 0);
+    case 4: return pick_v<4>(s.CPL, s.PF, s.DB != 0);
     }
     return nullptr;
 }
@@ -479,9 +565,18 @@ bool glm_plan(int64_t p, int64_t n, int requested_G, int num_cus, GlmLaunchShape
     if (G < 1) G = 1;
     if (G > num_cus) G = num_cus;
     s.G = G;
-    s.PF = 1;
-    while (s.PF < max_pf_for(s.V, s.CPL) && (int64_t)G * slots_per_group * s.PF < n) s.PF *= 2;
-    s.reduce_mode = ((int64_t)G * p * 4 <= 256 * 1024) ? kReduceRedundant : kReduceSliced;
+    // Rows each row slot must take per step.  If one register-resident group covers it, the whole next
+    // batch is prefetched across the exchange (no look-ahead needed); otherwise iterate with look-ahead.
+    const int64_t need = (n + (int64_t)G * slots_per_group - 1) / ((int64_t)G * slots_per_group);
+    if (s.CPL >= 8) {
+        s.PF = 1; s.DB = 0;
+    } else if (need <= max_pf(s.V, s.CPL, false)) {
+        s.PF = 1; s.DB = 0;
+        while (s.PF < need) s.PF *= 2;
+    } else {
+        s.PF = max_pf(s.V, s.CPL, true); s.DB = 1;
+    }
+    s.reduce_mode = ((int64_t)G * p <= 4096) ? kReduceRedundant : kReduceSliced;
     const int64_t th_len = std::max<int64_t>((p + 63) & ~int64_t(63), (int64_t)s.V * s.L * s.CPL);
     s.lds_bytes = (size_t)(th_len + (int64_t)(s.block / 64) * p + 64) * sizeof(float);
     if (s.lds_bytes < (size_t)(th_len + s.block + 64) * sizeof(float))

@@ -7,6 +7,8 @@
 // perm[(m-1) n : min(m n, rows)).
 #include "bmgd_internal.h"
 
+#include <algorithm>
+
 namespace bmgd {
 
 namespace {
@@ -54,7 +56,23 @@ __global__ void __launch_bounds__(256) perm_kernel(int32_t* __restrict__ out, ui
     out[(size_t)pass * rows + j] = (int32_t)x;
 }
 
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint4* __restrict__ dst, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
+}
+
 }  // namespace
+
+hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t stream)
+{
+    if (bytes == 0) return hipSuccess;
+    if ((reinterpret_cast<uintptr_t>(dst) % 16) != 0 || bytes % 16 != 0) return hipErrorInvalidValue;
+    const size_t n16 = bytes / 16;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 2048);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<uint4*>(dst), n16);
+    return hipGetLastError();
+}
 
 void perm_round_keys(uint64_t seed, uint32_t b, uint32_t t, uint32_t out[kPermRounds])
 {
