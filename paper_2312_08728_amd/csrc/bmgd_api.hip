@@ -243,15 +243,18 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         a.single_step = -1;
         a.ll_part = ctx->ll_part;
         a.ll_theta = ctx->ll_theta;
+        if ((int64_t)np * M >= (int64_t(1) << 23))
+            return fail(ctx, BMGD_EINVAL, "passes per launch * batches per pass must stay below 2^23; use a larger batch_n");
         if (ctx->chain == BMGD_CHAIN_PERSISTENT) {
             const int64_t nsteps = (int64_t)np * M;
-            if (nsteps >= 0x7FFFFFFFLL) return fail(ctx, BMGD_EINVAL, "too many steps in one launch");
             if ((uint64_t)ctx->tag_epoch + (uint64_t)nsteps + 1 >= 0xFFFFFFFFull) {
                 // tag space used up: clear the flagged words (stream-ordered) and start over
                 HIP_TRY(ctx, launch_fill_zero(ctx->ll_part, ctx->lay.sync - ctx->lay.ll_part, stream));
                 ctx->tag_epoch = 0;
             }
             a.tag_base = ctx->tag_epoch;
+            a.s_begin = 0;
+            a.s_end = (int)nsteps;
             ctx->tag_epoch += (uint32_t)nsteps;
             HIP_TRY(ctx, glm_launch_chain(ctx->shape, a, stream));
         } else {

@@ -36,7 +36,7 @@ struct GlmLaunchShape {
     int V;              // floats per vector load (1, 2, 4)
     int CPL;            // vector chunks of a row held per lane
     int PF;             // rows in flight per row slot
-    int DB;             // 1: look-ahead of one row group inside a step
+    int pipe;           // how row loads are scheduled against the theta chain (kPipe* in glm_kernels.hip)
     int L;              // lanes cooperating on one row (power of two <= 64)
     int block;          // threads per workgroup
     int G;              // workgroups
@@ -54,7 +54,8 @@ struct GlmArgs {
     unsigned long long* ll_part;   // [2][G][p] the same sums as flagged words {tag : float}, by step parity
     unsigned long long* ll_theta;  // [2][kThetaCopies][p] updated theta as flagged words (sliced reduction)
     unsigned* sync;         // [1] abort flag ([0] unused)
-    unsigned tag_base;      // tag of step s is tag_base + s + 1
+    unsigned tag_base;      // tag of step s is tag_base + (s - s_begin) + 1
+    int s_begin, s_end;     // steps of this launch: s in [s_begin, s_end), s = pass * M + batch, all < 2^23
     int rows, p, n, npass;
     int perm_stride;        // rows, or 0 when every pass reuses one partition
     int model;

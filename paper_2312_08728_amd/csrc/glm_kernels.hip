@@ -173,7 +173,17 @@ struct RowGroup {
     float y[PF];
 };
 
-template <int V, int CPL, int PF, bool THL, bool DB, int BLOCK>
+// PIPE selects how row loads are scheduled against the theta chain:
+//   kPipeWide   one row per slot, no look-ahead inside a step; the first row of the next step is requested
+//               before the exchange (wide rows: registers hold a single row);
+//   kPipeGroups several groups per step with one group of look-ahead; first group of the next step requested
+//               before the exchange;
+//   kPipeAhead  a whole step fits one register-resident group: rows are requested TWO steps ahead, right
+//               after an exchange completes, so neither the exchange (whose polls queue behind older loads
+//               of the same wavefront) nor the compute ever waits for HBM latency.
+enum { kPipeWide = 0, kPipeGroups = 1, kPipeAhead = 2 };
+
+template <int V, int CPL, int PF, bool THL, int PIPE, int BLOCK>
 __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
 {
     extern __shared__ __align__(16) float smem[];
@@ -196,10 +206,11 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
     const int pp = (p + 15) & ~15;                   // stride of flagged-word rows: writers own whole 128-byte lines
     const int th_len = max((p + 63) & ~63, V * L * CPL);
     float* th_lds = smem;                            // [th_len]
-    float* wpart = smem + th_len;                    // [NW][p], later reused as reduction scratch
+    float* wpart = smem + th_len;                    // [NW][p] per-wavefront sums
+    float* red = wpart + NW * p;                     // [BLOCK] scratch of the cross-workgroup sum
     const int M = (a.rows + a.n - 1) / a.n;
-    const int first = a.single_step >= 0 ? a.single_step : 0;
-    const int last = a.single_step >= 0 ? a.single_step + 1 : a.npass * M;
+    const int first = a.single_step >= 0 ? a.single_step : a.s_begin;
+    const int last = a.single_step >= 0 ? a.single_step + 1 : a.s_end;
 
     int col[CPL];
 #pragma unroll
@@ -219,9 +230,22 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
     load_theta_regs();
 
     // Batch geometry of step s.
-    auto batch_rows = [&](int s) { const int m = s % M; return min(a.n, a.rows - m * a.n); };
-    auto batch_base = [&](int s) { return (s / M) * a.perm_stride + (s % M) * a.n; };
-    auto batch_iters = [&](int s) { return (batch_rows(s) + S_total * PF - 1) / (S_total * PF); };
+    // Step s is mini-batch m = s mod M of pass t = s / M.  The chain is latency bound, so the quotient comes
+    // from a float reciprocal plus a correction (exact for s < 2^23, which the host guarantees) instead of
+    // an integer division, and the two possible group counts are computed once.
+    const float rcpM = 1.0f / (float)M;
+    auto split = [&](int s, int& t, int& m) {
+        t = (int)((float)s * rcpM);
+        m = s - t * M;
+        if (m >= M) { m -= M; ++t; }
+        if (m < 0) { m += M; --t; }
+    };
+    const int n_tail = a.rows - (M - 1) * a.n;
+    const int iters_full = (a.n + S_total * PF - 1) / (S_total * PF);
+    const int iters_tail = (n_tail + S_total * PF - 1) / (S_total * PF);
+    auto batch_rows = [&](int s) { int t, m; split(s, t, m); return m == M - 1 ? n_tail : a.n; };
+    auto batch_base = [&](int s) { int t, m; split(s, t, m); return t * a.perm_stride + m * a.n; };
+    auto batch_iters = [&](int s) { int t, m; split(s, t, m); return m == M - 1 ? iters_tail : iters_full; };
 
     // Row indices of group (s, it) for this lane's row slot; -1 where the slot has no row.
     auto load_idx = [&](int s, int it, int (&idx)[PF]) {
@@ -261,10 +285,20 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
         load_idx(in_step ? s : s + 1, in_step ? 1 : 0, idx);
     };
 
-    RowGroup<V, CPL, PF> cur, nxt;                   // nxt is only live when DB
+    constexpr bool DB = PIPE == kPipeGroups;
+    constexpr bool AHEAD = PIPE == kPipeAhead;
+    RowGroup<V, CPL, PF> cur, nxt;                   // nxt is not live with kPipeWide
     int idxn[PF];
     load_idx(first, 0, idxn);
     prefetch_step(first, cur, idxn);
+    if constexpr (AHEAD) prefetch_step(first + 1, nxt, idxn);
+    // after the exchange of step s: bring the rows a later step needs
+    auto advance_rows = [&](int s) {
+        if constexpr (AHEAD) {
+            cur = nxt;                               // rows of step s + 1, requested a whole step ago
+            prefetch_step(s + 2, nxt, idxn);
+        }
+    };
 
     PollGuard guard{a.sync + 1, a.timeout_ticks, 0, 0};
 
@@ -302,7 +336,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
                         if (g0 + u * NG < G) t += __builtin_bit_cast(float, (unsigned)w[u]);
                 }
                 if (dead) s_abort = 1;
-                wpart[gs * W + cj] = t;
+                red[gs * W + cj] = t;
             }
             __syncthreads();
             if (s_abort) return;
@@ -310,12 +344,12 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
                 float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;   // fixed association, four loads in flight
                 int q = 0;
                 for (; q + 4 <= NG; q += 4) {
-                    t0 += wpart[q * W + tid];
-                    t1 += wpart[(q + 1) * W + tid];
-                    t2 += wpart[(q + 2) * W + tid];
-                    t3 += wpart[(q + 3) * W + tid];
+                    t0 += red[q * W + tid];
+                    t1 += red[(q + 1) * W + tid];
+                    t2 += red[(q + 2) * W + tid];
+                    t3 += red[(q + 3) * W + tid];
                 }
-                for (; q < NG; ++q) t0 += wpart[q * W + tid];
+                for (; q < NG; ++q) t0 += red[q * W + tid];
                 apply(cb + tid, (t0 + t1) + (t2 + t3));
             }
             __syncthreads();
@@ -325,7 +359,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
     for (int s = first; s < last; ++s) {
         const int nb = batch_rows(s);
         const int iters = batch_iters(s);
-        const unsigned tag = a.tag_base + (unsigned)s + 1u;
+        const unsigned tag = a.tag_base + (unsigned)(s - first) + 1u;
         guard.arm();
         float acc[E];
 #pragma unroll
@@ -401,7 +435,8 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
                 th_lds[c] -= scale * t;
             }
             __syncthreads();
-            if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
+            if constexpr (AHEAD) advance_rows(s);
+            else if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
             load_theta_regs();
             continue;
         }
@@ -414,9 +449,9 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
             ll_store(words + (size_t)blockIdx.x * pp + c, t, tag);
         }
         // next step's rows do not depend on theta: in flight while the exchange resolves
-        if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
-        __syncthreads();                             // wpart is reused as scratch below
-
+        if constexpr (!AHEAD) {
+            if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
+        }
         if (a.reduce_mode == kReduceRedundant) {
             gather_columns(words, 0, p, tag, [&](int c, float t) { th_lds[c] -= scale * t; });
             if (s_abort) return;
@@ -449,6 +484,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
             __syncthreads();
             if (s_abort) return;
         }
+        if constexpr (AHEAD) advance_rows(s);
         load_theta_regs();
     }
 
@@ -471,53 +507,64 @@ __global__ void __launch_bounds__(256) glm_update_kernel(float* __restrict__ the
 using KernelFn = void (*)(GlmArgs);
 
 // Rows in flight per row slot are limited by registers: CPL * V * PF <= 16 floats per group (two groups
-// are live with look-ahead inside a step, DB), at most 4 rows with look-ahead; wide rows hold one row.
-constexpr bool shape_ok(int v, int cpl, int pf, bool db)
+// are live except with kPipeWide), at most 4 rows per group; wide rows (CPL >= 8) hold one row.
+constexpr bool shape_ok(int v, int cpl, int pf, int pipe)
 {
     const int e = v * cpl;
-    if (cpl >= 8) return pf == 1 && !db;
-    return e * pf <= 16 && (!db || pf <= 4);
+    if (cpl >= 8) return pf == 1 && pipe == kPipeWide;
+    if (pipe == kPipeWide) return false;
+    return e * pf <= 16 && pf <= 4;
 }
 
-int max_pf(int v, int cpl, bool db)
+int max_pf(int v, int cpl)
 {
     int pf = 1;
-    while (pf < 8 && shape_ok(v, cpl, pf * 2, db)) pf *= 2;
+    while (pf < 4 && shape_ok(v, cpl, pf * 2, kPipeGroups)) pf *= 2;
     return pf;
 }
 
-template <int V, int CPL, int PF, bool DB>
+template <int V, int CPL, int PF, int PIPE>
 KernelFn pick()
 {
-    if constexpr (!shape_ok(V, CPL, PF, DB)) {
+    if constexpr (!shape_ok(V, CPL, PF, PIPE)) {
         return nullptr;
     } else {
         constexpr bool wide = CPL >= 8;
-        return glm_chain_kernel<V, CPL, PF, wide, DB, wide ? 512 : 1024>;
+        return glm_chain_kernel<V, CPL, PF, wide, PIPE, wide ? 512 : 1024>;
     }
 }
 
+template <int V, int CPL, int PF>
+KernelFn pick_pipe(int pipe)
+{
+    switch (pipe) {
+    case kPipeWide: return pick<V, CPL, PF, kPipeWide>();
+    case kPipeGroups: return pick<V, CPL, PF, kPipeGroups>();
+    case kPipeAhead: return pick<V, CPL, PF, kPipeAhead>();
+    }
+    return nullptr;
+}
+
 template <int V, int CPL>
-KernelFn pick_pf(int pf, bool db)
+KernelFn pick_pf(int pf, int pipe)
 {
     switch (pf) {
-    case 1: return db ? pick<V, CPL, 1, true>() : pick<V, CPL, 1, false>();
-    case 2: return db ? pick<V, CPL, 2, true>() : pick<V, CPL, 2, false>();
-    case 4: return db ? pick<V, CPL, 4, true>() : pick<V, CPL, 4, false>();
-    case 8: return db ? pick<V, CPL, 8, true>() : pick<V, CPL, 8, false>();
+    case 1: return pick_pipe<V, CPL, 1>(pipe);
+    case 2: return pick_pipe<V, CPL, 2>(pipe);
+    case 4: return pick_pipe<V, CPL, 4>(pipe);
     }
     return nullptr;
 }
 
 template <int V>
-KernelFn pick_v(int cpl, int pf, bool db)
+KernelFn pick_v(int cpl, int pf, int pipe)
 {
     switch (cpl) {
-    case 1: return pick_pf<V, 1>(pf, db);
-    case 2: return pick_pf<V, 2>(pf, db);
-    case 4: return pick_pf<V, 4>(pf, db);
-    case 8: return pick_pf<V, 8>(pf, db);
-    case 16: return pick_pf<V, 16>(pf, db);
+    case 1: return pick_pf<V, 1>(pf, pipe);
+    case 2: return pick_pf<V, 2>(pf, pipe);
+    case 4: return pick_pf<V, 4>(pf, pipe);
+    case 8: return pick_pf<V, 8>(pf, pipe);
+    case 16: return pick_pf<V, 16>(pf, pipe);
     }
     return nullptr;
 }
@@ -525,9 +572,9 @@ KernelFn pick_v(int cpl, int pf, bool db)
 KernelFn pick_kernel(const GlmLaunchShape& s)
 {
     switch (s.V) {
-    case 1: return pick_v<1>(s.CPL, s.PF, s.DB != 0);
-    case 2: return pick_v<2>(s.CPL, s.PF, s.DB != 0);
-    case 4: return pick_v<4>(s.CPL, s.PF, s.DB != 0);
+    case 1: return pick_v<1>(s.CPL, s.PF, s.pipe);
+    case 2: return pick_v<2>(s.CPL, s.PF, s.pipe);
+    case 4: return pick_v<4>(s.CPL, s.PF, s.pipe);
     }
     return nullptr;
 }
@@ -559,8 +606,10 @@ bool glm_plan(int64_t p, int64_t n, int requested_G, int num_cus, GlmLaunchShape
     const int slots_per_group = (s.block / 64) * (64 / s.L);
     int G = requested_G;
     if (G <= 0) {
+        // measured on MI355X: a compute unit sustains ~19 GB/s of gathered rows, one exchange costs 1.5-3 us;
+        // about 12 KB of rows per workgroup and step balances the two
         const int64_t bytes = n * p * 4;
-        G = (int)((bytes + 32767) / 32768);
+        G = (int)std::min<int64_t>((bytes + 12287) / 12288, 1 << 20);
     }
     if (G < 1) G = 1;
     if (G > num_cus) G = num_cus;
@@ -569,18 +618,16 @@ bool glm_plan(int64_t p, int64_t n, int requested_G, int num_cus, GlmLaunchShape
     // batch is prefetched across the exchange (no look-ahead needed); otherwise iterate with look-ahead.
     const int64_t need = (n + (int64_t)G * slots_per_group - 1) / ((int64_t)G * slots_per_group);
     if (s.CPL >= 8) {
-        s.PF = 1; s.DB = 0;
-    } else if (need <= max_pf(s.V, s.CPL, false)) {
-        s.PF = 1; s.DB = 0;
+        s.PF = 1; s.pipe = kPipeWide;
+    } else if (need <= max_pf(s.V, s.CPL)) {
+        s.PF = 1; s.pipe = kPipeAhead;
         while (s.PF < need) s.PF *= 2;
     } else {
-        s.PF = max_pf(s.V, s.CPL, true); s.DB = 1;
+        s.PF = max_pf(s.V, s.CPL); s.pipe = kPipeGroups;
     }
     s.reduce_mode = ((int64_t)G * p <= 4096) ? kReduceRedundant : kReduceSliced;
     const int64_t th_len = std::max<int64_t>((p + 63) & ~int64_t(63), (int64_t)s.V * s.L * s.CPL);
-    s.lds_bytes = (size_t)(th_len + (int64_t)(s.block / 64) * p + 64) * sizeof(float);
-    if (s.lds_bytes < (size_t)(th_len + s.block + 64) * sizeof(float))
-        s.lds_bytes = (size_t)(th_len + s.block + 64) * sizeof(float);
+    s.lds_bytes = (size_t)(th_len + (int64_t)(s.block / 64) * p + s.block + 64) * sizeof(float);
     *out = s;
     return true;
 }
