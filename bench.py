@@ -1,0 +1,291 @@
+"""Throughput of the BMGD computation step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+
+One *step* is one buffer taken through the whole hot path: the device-side partitions for its T passes
+and the chain of T * M sequential mini-batch updates (eq. (2.1)).  Buffers are resident in HBM when the
+timed region starts (bmgd_run_device_buffer); the pinned-host loader is measured separately and reported
+under "h2d".  Prints ONE JSON line.
+
+Metric: sample-gradients per second = rows visited by mini-batch updates per second (R * T * N of
+Algorithm 1 per whole run), plus the achieved algorithmic HBM rate of the fused gradient kernel.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+# HBM traffic of one launch of the chain kernel on the primary workload, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE (see profiles/); only valid for the kernel source it was measured on.
+TRAFFIC = {"cfg2": {"kernel_sha256": "ce1906b8f5a746d559ab3c14e251353e1866665b3d23698ac577cb010e924e3f", "bytes_per_launch": 235960499}}
+
+
+def _kernel_sha() -> str:
+    h = hashlib.sha256()
+    for f in ("glm_kernels.hip", "bmgd_api.hip", "perm_kernel.hip"):
+        with open(os.path.join(ROOT, "paper_2312_08728_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def _algorithmic_bytes_per_sample_gradient(w) -> int:
+    # one read of the row (p values) + its response + its index in the partition
+    return w.p * w.x_itemsize + 4 + 4
+
+
+def _device_buffers(w, nbuf, from_host=None):
+    """nbuf buffers of the workload in HBM: from the seeded host generator, or drawn on the device."""
+    import torch
+    import workloads as wl
+    bufs = []
+    if from_host is not None:
+        X, y = from_host
+        for k in range(nbuf):
+            lo, hi = wl.buffer_rows(w, k % w.K)
+            bufs.append((torch.from_numpy(X[lo:hi]).cuda(), torch.from_numpy(y[lo:hi]).cuda(), hi - lo))
+        return bufs
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.seed)
+    theta = torch.randn(w.p, device="cuda", generator=g) / w.p ** 0.5
+    for k in range(nbuf):
+        X = torch.randn(w.N0, w.p, device="cuda", generator=g)
+        eta = X @ theta
+        if w.model == wl.LOGISTIC:
+            y = (torch.rand(w.N0, device="cuda", generator=g) < torch.sigmoid(eta)).float()
+        else:
+            y = eta + w.noise_sigma * torch.randn(w.N0, device="cuda", generator=g)
+        bufs.append((X, y, w.N0))
+    return bufs
+
+
+def _time_resident(w, bufs, steps, warmup):
+    """Run `steps` buffers (cycling over bufs) after `warmup`; returns (seconds, stats delta, theta)."""
+    import torch
+    import paper_2312_08728_amd as B
+    ctx = B.Context(w.p, w.N0, w.n, w.alpha, w.T, model=w.model, n_classes=w.C, seed=w.seed, n_buffers=w.K)
+    try:
+        s = torch.cuda.Stream()
+        for i in range(warmup):
+            X, y, rows = bufs[i % len(bufs)]
+            ctx.run_device_buffer(X, y, rows, s)
+        ctx.sync()
+        if warmup:
+            # timed run starts from the same state a fresh run would: theta = 0, buffer counter 0
+            ctx.set_theta([0.0] * ctx.theta_len)
+            ctx.set_position(0)
+        st0 = ctx.stats()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            X, y, rows = bufs[i % len(bufs)]
+            ctx.run_device_buffer(X, y, rows, s)
+        ctx.sync()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        st1 = ctx.stats()
+        theta = ctx.get_theta()
+        delta = {
+            "sample_gradients": st1.sample_gradients - st0.sample_gradients,
+            "minibatch_steps": st1.steps - st0.steps,
+            "chain_ms": st1.chain_ms - st0.chain_ms,
+            "chain_launches": st1.chain_launches - st0.chain_launches,
+            "compute_ms": st1.compute_ms - st0.compute_ms,
+            "n_workgroups": st1.n_workgroups, "threads_per_group": st1.threads_per_group,
+        }
+        return dt, delta, theta
+    finally:
+        ctx.close()
+
+
+def _roofline(w, delta, traffic=None):
+    per_launch_s = delta["chain_ms"] / 1e3 / max(delta["chain_launches"], 1)
+    bytes_per_launch = _algorithmic_bytes_per_sample_gradient(w) * delta["sample_gradients"] / max(delta["chain_launches"], 1)
+    achieved = bytes_per_launch / per_launch_s / 1e9
+    return {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
+            "kernel": "glm_chain_kernel", "avg_launch_ms": round(per_launch_s * 1e3, 4),
+            "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+
+
+def _time_pipelined(w, X, y, steps):
+    """Same buffers through the pinned-host loader on its own stream; returns overlap figures."""
+    import torch
+    import workloads as wl
+    import paper_2312_08728_amd as B
+    xp, yp = torch.from_numpy(X).pin_memory(), torch.from_numpy(y).pin_memory()
+    out = {}
+    for mode in ("h2d_only", "pipelined"):
+        # "h2d_only": the same copies with next to no compute behind them (one full-batch update per buffer)
+        alone = mode == "h2d_only"
+        ctx = B.Context(w.p, w.N0, w.N0 if alone else w.n, w.alpha, 1 if alone else w.T, model=w.model,
+                        n_classes=w.C, seed=w.seed, n_buffers=w.K)
+        try:
+            cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                lo, hi = wl.buffer_rows(w, i % w.K)
+                ctx.load_buffer_async(xp[lo:hi], yp[lo:hi], hi - lo, cs)
+                ctx.run_buffer(ks)
+            ctx.sync()
+            dt = time.perf_counter() - t0
+            st = ctx.stats()
+            out[mode] = {"seconds": dt, "copy_ms": st.copy_ms, "wait_ms": st.wait_ms, "compute_ms": st.compute_ms,
+                         "h2d_bytes": st.h2d_bytes}
+        finally:
+            ctx.close()
+    return out
+
+
+def _cpu_baseline(w, X, y, budget_s=20.0):
+    """The fp64 oracle, as it stands, on the same stored inputs; bounded to about budget_s of CPU time."""
+    import numpy as np
+    from oracle import bmgd as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([int(t.get("num_threads", 1)) for t in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    st = O.BMGD(w.model, w.p, w.n, w.alpha, w.T, C=w.C, seed=w.seed)
+    import workloads as wl
+    t0 = time.perf_counter()
+    done_sg = 0
+    buffers = 0
+    full = True
+    for r in range(w.R):
+        for k in range(w.K):
+            lo, hi = wl.buffer_rows(w, k)
+            st.run_buffer(X[lo:hi], y[lo:hi])
+            done_sg += w.T * (hi - lo)
+            buffers += 1
+            if time.perf_counter() - t0 > budget_s and buffers < w.R * w.K:
+                full = False
+                break
+        if not full:
+            break
+    dt = time.perf_counter() - t0
+    sample = (f"whole {w.name} run ({buffers} buffers)" if full
+              else f"first {buffers} of {w.R * w.K} buffers of {w.name} (time-bounded)")
+    return {"value": round(done_sg / dt, 1), "unit": "sample-gradients/s", "cores": threads, "kind": "oracle",
+            "sample": sample, "seconds": round(dt, 3)}, (st.theta if full else None)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="buffers to time (default: one whole run, R*K)")
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the short cfg1/cfg3/cfg4 side measurements")
+    ap.add_argument("--no-h2d", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain elementwise copy of 1 GiB (5 launches): the known-size kernel that "
+                         "hardware-counter readings of HBM traffic are scaled by")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the method's step chain is sequential and no "
+              "collectives are built); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU available", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB read, 1 GiB written per launch
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_launch": src.numel() * 4,
+                                               "bytes_written_per_launch": dst.numel() * 4, "launches": 5}}))
+        return 0
+
+    w = wl.CONFIGS[args.workload]
+    steps = args.steps if args.steps is not None else w.R * w.K
+    X, y = wl.dataset(w)
+    bufs = _device_buffers(w, w.K, from_host=(X, y))
+    dt, delta, theta = _time_resident(w, bufs, steps, args.warmup)
+    del bufs
+    torch.cuda.empty_cache()
+
+    tr = TRAFFIC.get(w.name, {})
+    traffic = tr.get("bytes_per_launch") if tr.get("kernel_sha256") == _kernel_sha() else None
+    result = {
+        "metric": "sample-gradients/sec (BMGD computation step, buffers resident in HBM)",
+        "value": round(delta["sample_gradients"] / dt, 1),
+        "unit": "sample-gradients/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": round(dt * 1e3 / steps, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.x_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {wl.MODEL_NAMES[w.model]} regression N={w.N} p={w.p} buffer={w.N0} "
+                               f"batch={w.n} passes={w.T} lr={w.alpha} (a step = one buffer = {w.T * w.M} mini-batch updates)",
+                   "minibatch_updates_timed": delta["minibatch_steps"],
+                   "us_per_minibatch_update": round(dt * 1e6 / max(delta["minibatch_steps"], 1), 3),
+                   "workgroups": delta["n_workgroups"], "threads_per_group": delta["threads_per_group"]},
+        "roofline": _roofline(w, delta, traffic),
+    }
+
+    if not args.no_cpu_baseline:
+        base, theta_cpu = _cpu_baseline(w, X, y)
+        result["cpu_baseline"] = base
+        if theta_cpu is not None and steps == w.R * w.K:
+            d = np.linalg.norm(theta.astype(np.float64).ravel() - theta_cpu.ravel()) / np.linalg.norm(theta_cpu)
+            result["parity_rel_l2_vs_oracle"] = float(f"{d:.3e}")
+
+    if not args.no_h2d:
+        pl = _time_pipelined(w, X, y, min(steps, w.K * 2))
+        h2d_alone = pl["h2d_only"]["copy_ms"]
+        nb = min(steps, w.K * 2)
+        comp_alone = delta["compute_ms"] / steps * nb
+        piped = pl["pipelined"]
+        hidden = 1.0 - piped["wait_ms"] / max(piped["copy_ms"], 1e-9)
+        ceiling = min(1.0, comp_alone / max(h2d_alone, 1e-9))
+        overlap_eff = (h2d_alone + comp_alone - piped["seconds"] * 1e3) / max(min(h2d_alone, comp_alone), 1e-9)
+        result["h2d"] = {"buffers": nb, "h2d_gbs": round(piped["h2d_bytes"] / max(piped["copy_ms"], 1e-9) / 1e6, 2),
+                         "copy_ms": round(piped["copy_ms"], 3), "compute_ms_alone": round(comp_alone, 3),
+                         "pipelined_ms": round(piped["seconds"] * 1e3, 3),
+                         "frac_h2d_hidden": round(hidden, 4), "ceiling_at_this_T": round(ceiling, 4),
+                         "overlap_efficiency": round(overlap_eff, 4)}
+    del X, y
+
+    if not args.no_others:
+        others = {}
+        for name, nbuf in (("cfg1", 5), ("cfg3", 2), ("cfg4", 2)):
+            wo = wl.CONFIGS[name]
+            try:
+                ob = _device_buffers(wo, nbuf)
+                odt, od, _ = _time_resident(wo, ob, nbuf, 1)
+                rf = _roofline(wo, od)
+                others[name] = {"value": round(od["sample_gradients"] / odt, 1), "ms_per_step": round(odt * 1e3 / nbuf, 4),
+                                "us_per_minibatch_update": round(odt * 1e6 / od["minibatch_steps"], 3),
+                                "roofline_frac": rf["frac"], "achieved_gbs": rf["achieved"],
+                                "workgroups": od["n_workgroups"], "data": "synthetic, drawn on the device"}
+                del ob
+                torch.cuda.empty_cache()
+            except Exception as e:  # a side measurement must not lose the main line
+                others[name] = {"error": str(e)[:200]}
+        result["other_workloads"] = others
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -76,7 +76,7 @@ enum {
 /* how the sequential chain of mini-batch steps is driven */
 enum {
     BMGD_CHAIN_AUTO = 0,
-    BMGD_CHAIN_PERSISTENT = 1,   /* one cooperative kernel per buffer, grid-wide barrier per step */
+    BMGD_CHAIN_PERSISTENT = 1,   /* one persistent kernel per buffer; workgroups exchange sums once per step */
     BMGD_CHAIN_LAUNCH = 2        /* kernel launches per step, in stream order */
 };
 
@@ -119,6 +119,9 @@ typedef struct bmgd_stats {
     int32_t threads_per_group;
     int32_t chain;             /* resolved BMGD_CHAIN_* */
     int32_t reserved;
+    double  chain_ms;          /* device time inside the chain kernels alone (events around each launch of the
+                                  persistent kernel; in step-per-launch mode: around each pass-chunk of launches) */
+    int64_t chain_launches;    /* number of such timed launches */
 } bmgd_stats;
 
 /* Fill *cfg with defaults: linear model, fp32, 1 class, seed 0, per-pass reshuffle, automatic launch
@@ -131,7 +134,8 @@ bmgd_ctx* bmgd_create(int64_t p, int64_t buffer_n, int64_t batch_n, double lr, i
 
 /* Full form.  *out receives the context.  Errors: BMGD_EINVAL (see field comments; also p above the
  * supported maximum: 4096 if p % 4 == 0, 2048 if p % 2 == 0, else 1024 for the GLM models),
- * BMGD_EHIP, BMGD_ENOMEM. */
+ * BMGD_EHIP, BMGD_ENOMEM.  Also BMGD_EINVAL from the run calls when min(passes, 4) * ceil(rows / batch_n)
+ * reaches 2^23 (step indices inside one kernel launch are kept below that). */
 int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out);
 
 /* Device bytes a context with this configuration needs (two buffer slots, partitions, theta, scratch);

@@ -46,7 +46,7 @@ class bmgd_stats(C.Structure):
         ("buffers_run", C.c_int64), ("steps", C.c_int64), ("sample_gradients", C.c_int64),
         ("h2d_bytes", C.c_int64), ("copy_ms", C.c_double), ("compute_ms", C.c_double),
         ("wait_ms", C.c_double), ("n_workgroups", C.c_int32), ("threads_per_group", C.c_int32),
-        ("chain", C.c_int32), ("reserved", C.c_int32),
+        ("chain", C.c_int32), ("reserved", C.c_int32), ("chain_ms", C.c_double), ("chain_launches", C.c_int64),
     ]
 
 

@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <new>
 #include <string>
+#include <utility>
 #include <vector>
 
 using namespace bmgd;
@@ -66,7 +67,9 @@ struct bmgd_ctx {
     int chain = BMGD_CHAIN_PERSISTENT;
     int64_t buffer_counter = 0;
     int64_t steps = 0, sample_gradients = 0, h2d_bytes = 0;
-    double copy_ms = 0, compute_ms = 0, wait_ms = 0;
+    double copy_ms = 0, compute_ms = 0, wait_ms = 0, chain_ms = 0;
+    int64_t chain_launches = 0;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> open_chain;   // events around chain launches, unsettled
     hipEvent_t base = nullptr;
     std::vector<RunRecord> open_records;
     std::vector<hipEvent_t> event_pool;
@@ -187,6 +190,12 @@ void settle_records(bmgd_ctx* ctx)
         give_event(ctx, r.ready); give_event(ctx, r.start); give_event(ctx, r.end);
     }
     ctx->open_records.clear();
+    for (auto& pr : ctx->open_chain) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) { ctx->chain_ms += ms; ctx->chain_launches += 1; }
+        give_event(ctx, pr.first); give_event(ctx, pr.second);
+    }
+    ctx->open_chain.clear();
 }
 
 int drain(bmgd_ctx* ctx)
@@ -224,6 +233,8 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
             for (int i = 0; i < nperm; ++i) perm_round_keys(c.seed, b, fixed ? 0u : (uint32_t)(t0 + i + 1), keys.key[i]);
             HIP_TRY(ctx, launch_perm(ctx->perm, rows, nperm, keys, stream));
         }
+        hipEvent_t ev0 = take_event(ctx), ev1 = take_event(ctx);
+        if (!ev0 || !ev1) return fail(ctx, BMGD_EHIP, "could not create events");
         GlmArgs a{};
         a.X = static_cast<const float*>(x);
         a.y = static_cast<const float*>(y);
@@ -245,6 +256,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         a.ll_theta = ctx->ll_theta;
         if ((int64_t)np * M >= (int64_t(1) << 23))
             return fail(ctx, BMGD_EINVAL, "passes per launch * batches per pass must stay below 2^23; use a larger batch_n");
+        HIP_TRY(ctx, hipEventRecord(ev0, stream));
         if (ctx->chain == BMGD_CHAIN_PERSISTENT) {
             const int64_t nsteps = (int64_t)np * M;
             if ((uint64_t)ctx->tag_epoch + (uint64_t)nsteps + 1 >= 0xFFFFFFFFull) {
@@ -265,6 +277,8 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
                 HIP_TRY(ctx, glm_launch_step(ctx->shape, a, nb, stream));
             }
         }
+        HIP_TRY(ctx, hipEventRecord(ev1, stream));
+        ctx->open_chain.emplace_back(ev0, ev1);
     }
     ctx->steps += (int64_t)c.passes * M;
     ctx->sample_gradients += (int64_t)c.passes * rows;
@@ -553,6 +567,8 @@ BMGD_API int bmgd_get_stats(bmgd_ctx* ctx, bmgd_stats* out)
     out->n_workgroups = ctx->shape.G;
     out->threads_per_group = ctx->shape.block;
     out->chain = ctx->chain;
+    out->chain_ms = ctx->chain_ms;
+    out->chain_launches = ctx->chain_launches;
     return rc;
 }
 

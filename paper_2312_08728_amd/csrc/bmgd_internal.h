@@ -70,7 +70,7 @@ struct GlmArgs {
 bool glm_plan(int64_t p, int64_t n, int requested_G, int num_cus, GlmLaunchShape* out, char* why, size_t why_len);
 // Query co-residency and set attributes; fills shape->max_G and clamps shape->G.
 hipError_t glm_prepare(GlmLaunchShape* shape);
-// One cooperative launch covering npass passes over the buffer.
+// One launch of the persistent chain kernel covering steps [s_begin, s_end) of the buffer.
 hipError_t glm_launch_chain(const GlmLaunchShape& shape, const GlmArgs& args, hipStream_t stream);
 // Step-per-launch variant: partial sums for step `args.single_step`, then reduce + update.
 hipError_t glm_launch_step(const GlmLaunchShape& shape, const GlmArgs& args, int nb, hipStream_t stream);

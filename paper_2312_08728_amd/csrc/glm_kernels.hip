@@ -3,7 +3,7 @@
 // One step of eq. (2.1): theta <- theta - alpha/n_b * sum_{i in batch} (b'(x_i'theta) - y_i) x_i, with
 // b' the identity (eq. (3.1)) or the sigmoid (Section 3.2.3).  The steps of a pass, and the passes of a
 // buffer, depend on each other through theta (Algorithm 1's inner loops), so the whole chain for one
-// buffer runs inside ONE cooperative kernel: workgroups stay resident, each mini-batch is spread over all
+// buffer runs inside ONE persistent kernel: all workgroups are resident at once, each mini-batch is spread over all
 // of them, and a grid-wide barrier per step stands where a kernel boundary would otherwise be.
 //
 // Data path of a step (per row, read from HBM exactly once):
@@ -661,9 +661,12 @@ hipError_t glm_launch_chain(const GlmLaunchShape& s, const GlmArgs& args, hipStr
     if (!fn || s.G < 1 || s.G > s.max_G) return hipErrorInvalidValue;
     GlmArgs a = args;
     a.single_step = -1;
-    void* params[] = {&a};
-    return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(fn), dim3(s.G), dim3(s.block), params,
-                                      (unsigned)s.lds_bytes, stream);
+    // An ordinary launch: s.G <= s.max_G (checked above) means every workgroup fits on the device at once,
+    // so all of them become resident as soon as compute units are free, and each device-side wait is
+    // bounded anyway.  (The runtime's cooperative-launch path is avoided: it brings nothing more here and
+    // its dedicated queue does not tear down cleanly under the profiler.)
+    hipLaunchKernelGGL(fn, dim3(s.G), dim3(s.block), s.lds_bytes, stream, a);
+    return hipGetLastError();
 }
 
 hipError_t glm_launch_step(const GlmLaunchShape& s, const GlmArgs& args, int nb, hipStream_t stream)
