@@ -25,7 +25,7 @@ constexpr int kMaxGroups = 256;                    // upper bound used to size t
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, aux, total;
+    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, total;
 };
 
 struct Slot {
@@ -62,6 +62,10 @@ struct bmgd_ctx {
     unsigned long long* ll_part = nullptr;
     unsigned long long* ll_theta = nullptr;
     unsigned* sync = nullptr;
+    void* wbt = nullptr;                           // softmax: bf16 copy of W, transposed
+    float* u = nullptr;                            // softmax: logits scratch
+    void* rt = nullptr;                            // softmax: residual scratch
+    void* xt = nullptr;                            // softmax: transposed mini-batches of one pass
     uint32_t tag_epoch = 0;                        // tags handed out so far for flagged-word exchanges
     GlmLaunchShape shape{};
     int chain = BMGD_CHAIN_PERSISTENT;
@@ -91,8 +95,10 @@ bool valid_config(const bmgd_config& c, std::string* why)
     if (c.passes < 1) return bad("passes must be at least 1");
     if (c.model != BMGD_LINEAR && c.model != BMGD_LOGISTIC && c.model != BMGD_SOFTMAX) return bad("unknown model");
     if (c.model == BMGD_SOFTMAX) {
-        if (c.n_classes < 2) return bad("softmax needs n_classes >= 2");
+        if (c.n_classes < 2 || c.n_classes > 2048) return bad("softmax needs 2 <= n_classes <= 2048");
         if (c.x_dtype != BMGD_BF16) return bad("softmax takes bf16 predictors");
+        if (c.p % 8 != 0) return bad("softmax needs p to be a multiple of 8 (16-byte rows of bf16)");
+        if ((double)c.p * 2048.0 * 4.0 > 8.0e9) return bad("p too large for softmax");
     } else if (c.x_dtype != BMGD_F32) {
         return bad("linear and logistic models take fp32 predictors");
     }
@@ -128,13 +134,25 @@ Layout make_layout(const bmgd_config& c)
     }
     const int np = std::min<int>(c.passes, kMaxPassesPerLaunch);
     l.perm = off;    off += align_up((size_t)np * c.buffer_n * 4);
-    l.theta = off;   off += align_up((size_t)c.p * C * 4);
-    l.partial = off; off += align_up((size_t)2 * kMaxGroups * c.p * 4);
-    const size_t pp = ((size_t)c.p + 15) & ~size_t(15);   // flagged-word rows are padded to whole 128-byte lines
-    l.ll_part = off; off += align_up((size_t)2 * kMaxGroups * pp * 8);
-    l.ll_theta = off; off += align_up((size_t)2 * kThetaCopies * pp * 8);
-    l.sync = off;    off += align_up(64);
-    l.aux = off;
+    if (c.model == BMGD_SOFTMAX) {
+        const SoftmaxDims d = softmax_dims(c.p, c.batch_n, C);
+        const size_t m_max = (size_t)((c.buffer_n + c.batch_n - 1) / c.batch_n);
+        l.theta = off;   off += align_up((size_t)c.p * d.c_pad * 4);             // fp32 master, [p][c_pad]
+        l.partial = l.ll_part = l.ll_theta = off;
+        l.sync = off;    off += align_up(64);
+        l.wbt = off;     off += align_up((size_t)d.c_pad * d.p_pad * 2);
+        l.u = off;       off += align_up((size_t)8 * d.m_pad * d.c_pad * 4);
+        l.rt = off;      off += align_up((size_t)d.c_pad * d.n_pad * 2);
+        l.xt = off;      off += align_up(m_max * (size_t)c.p * d.n_pad * 2);
+    } else {
+        l.theta = off;   off += align_up((size_t)c.p * 4);
+        l.partial = off; off += align_up((size_t)2 * kMaxGroups * c.p * 4);
+        const size_t pp = ((size_t)c.p + 15) & ~size_t(15);   // flagged-word rows are padded to whole 128-byte lines
+        l.ll_part = off; off += align_up((size_t)2 * kMaxGroups * pp * 8);
+        l.ll_theta = off; off += align_up((size_t)2 * kThetaCopies * pp * 8);
+        l.sync = off;    off += align_up(64);
+        l.wbt = l.u = l.rt = l.xt = off;
+    }
     l.total = off;
     return l;
 }
@@ -235,6 +253,37 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         }
         hipEvent_t ev0 = take_event(ctx), ev1 = take_event(ctx);
         if (!ev0 || !ev1) return fail(ctx, BMGD_EHIP, "could not create events");
+        if (c.model == BMGD_SOFTMAX) {
+            HIP_TRY(ctx, hipEventRecord(ev0, stream));
+            const SoftmaxDims d = softmax_dims(c.p, n, c.n_classes);
+            const SoftmaxDims dmax = softmax_dims(c.p, c.batch_n, c.n_classes);
+            for (int i = 0; i < np; ++i) {
+                const int32_t* pm = ctx->perm + (fixed ? 0 : (size_t)i * rows);
+                HIP_TRY(ctx, softmax_permute_transpose(x, pm, ctx->xt, (int)rows, (int)c.p, (int)n, d, stream));
+                for (int64_t m = 0; m < M; ++m) {
+                    SoftmaxStep st{};
+                    st.X = x;
+                    st.y = static_cast<const int32_t*>(y);
+                    st.idx = pm + m * n;
+                    st.XT = static_cast<const char*>(ctx->xt) + (size_t)m * c.p * d.n_pad * 2;
+                    st.W = ctx->theta;
+                    st.WbT = ctx->wbt;
+                    st.U = ctx->u;
+                    st.Rt = ctx->rt;
+                    st.nb = (int)std::min<int64_t>(n, rows - m * n);
+                    st.p = (int)c.p;
+                    st.C = c.n_classes;
+                    st.alpha = (float)c.lr;
+                    SoftmaxDims ds = d;
+                    ds.c_pad = dmax.c_pad;           // W and WbT keep the strides fixed at creation
+                    ds.p_pad = dmax.p_pad;
+                    HIP_TRY(ctx, softmax_step(st, ds, stream));
+                }
+            }
+            HIP_TRY(ctx, hipEventRecord(ev1, stream));
+            ctx->open_chain.emplace_back(ev0, ev1);
+            continue;
+        }
         GlmArgs a{};
         a.X = static_cast<const float*>(x);
         a.y = static_cast<const float*>(y);
@@ -335,7 +384,6 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     if (!cfg || !out) return fail(nullptr, BMGD_EINVAL, "cfg and out must not be NULL");
     std::string why;
     if (!valid_config(*cfg, &why)) return fail(nullptr, BMGD_EINVAL, why);
-    if (cfg->model == BMGD_SOFTMAX) return fail(nullptr, BMGD_EINVAL, "softmax is not available in this build of the library");
 
     int ndev = 0;
     hipError_t e = hipGetDeviceCount(&ndev);
@@ -389,20 +437,35 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->ll_part = reinterpret_cast<unsigned long long*>(base + ctx->lay.ll_part);
     ctx->ll_theta = reinterpret_cast<unsigned long long*>(base + ctx->lay.ll_theta);
     ctx->sync = reinterpret_cast<unsigned*>(base + ctx->lay.sync);
-    CREATE_TRY(hipMemset(ctx->theta, 0, (size_t)ctx->theta_len * 4));
+    ctx->wbt = base + ctx->lay.wbt;
+    ctx->u = reinterpret_cast<float*>(base + ctx->lay.u);
+    ctx->rt = base + ctx->lay.rt;
+    ctx->xt = base + ctx->lay.xt;
     CREATE_TRY(hipMemset(ctx->sync, 0, 64));
-    // flagged words start with tag 0, which no step ever waits for
-    CREATE_TRY(hipMemset(ctx->ll_part, 0, ctx->lay.sync - ctx->lay.ll_part));
+    if (cfg->model == BMGD_SOFTMAX) {
+        // theta = 0 (padding classes included), bf16 copy = 0, residual scratch = 0
+        CREATE_TRY(hipMemset(ctx->theta, 0, ctx->lay.sync - ctx->lay.theta));
+        CREATE_TRY(hipMemset(ctx->wbt, 0, ctx->lay.xt - ctx->lay.wbt));
+    } else {
+        CREATE_TRY(hipMemset(ctx->theta, 0, (size_t)ctx->theta_len * 4));
+        // flagged words start with tag 0, which no step ever waits for
+        CREATE_TRY(hipMemset(ctx->ll_part, 0, ctx->lay.sync - ctx->lay.ll_part));
+    }
     CREATE_TRY(hipEventCreate(&ctx->base));
     CREATE_TRY(hipEventRecord(ctx->base, nullptr));
 
-    char msg[160];
-    if (!glm_plan(cfg->p, cfg->batch_n, cfg->n_workgroups, ctx->num_cus, &ctx->shape, msg, sizeof msg)) {
-        ctx->err = msg;
-        return bail(BMGD_EINVAL);
+    if (cfg->model == BMGD_SOFTMAX) {
+        CREATE_TRY(softmax_prepare(softmax_dims(cfg->p, cfg->batch_n, cfg->n_classes)));
+        ctx->chain = BMGD_CHAIN_LAUNCH;              // three launches per mini-batch update, in stream order
+    } else {
+        char msg[160];
+        if (!glm_plan(cfg->p, cfg->batch_n, cfg->n_workgroups, ctx->num_cus, &ctx->shape, msg, sizeof msg)) {
+            ctx->err = msg;
+            return bail(BMGD_EINVAL);
+        }
+        CREATE_TRY(glm_prepare(&ctx->shape));
+        ctx->chain = cfg->chain == BMGD_CHAIN_AUTO ? BMGD_CHAIN_PERSISTENT : cfg->chain;
     }
-    CREATE_TRY(glm_prepare(&ctx->shape));
-    ctx->chain = cfg->chain == BMGD_CHAIN_AUTO ? BMGD_CHAIN_PERSISTENT : cfg->chain;
     CREATE_TRY(hipDeviceSynchronize());
 #undef CREATE_TRY
     *out = ctx;
@@ -513,6 +576,12 @@ BMGD_API int bmgd_get_theta(bmgd_ctx* ctx, float* host_out, int64_t len)
     if (len != ctx->theta_len) return fail(ctx, BMGD_EINVAL, "len must equal p (p * n_classes for softmax)");
     const int rc = drain(ctx);
     if (rc != BMGD_OK) return rc;
+    if (ctx->cfg.model == BMGD_SOFTMAX) {
+        const SoftmaxDims d = softmax_dims(ctx->cfg.p, ctx->cfg.batch_n, ctx->cfg.n_classes);
+        const size_t C = (size_t)ctx->cfg.n_classes;
+        HIP_TRY(ctx, hipMemcpy2D(host_out, C * 4, ctx->theta, (size_t)d.c_pad * 4, C * 4, (size_t)ctx->cfg.p, hipMemcpyDeviceToHost));
+        return BMGD_OK;
+    }
     HIP_TRY(ctx, hipMemcpy(host_out, ctx->theta, (size_t)len * 4, hipMemcpyDeviceToHost));
     return BMGD_OK;
 }
@@ -524,6 +593,14 @@ BMGD_API int bmgd_set_theta(bmgd_ctx* ctx, const float* host_in, int64_t len)
     if (len != ctx->theta_len) return fail(ctx, BMGD_EINVAL, "len must equal p (p * n_classes for softmax)");
     const int rc = drain(ctx);
     if (rc != BMGD_OK) return rc;
+    if (ctx->cfg.model == BMGD_SOFTMAX) {
+        const SoftmaxDims d = softmax_dims(ctx->cfg.p, ctx->cfg.batch_n, ctx->cfg.n_classes);
+        const size_t C = (size_t)ctx->cfg.n_classes;
+        HIP_TRY(ctx, hipMemcpy2D(ctx->theta, (size_t)d.c_pad * 4, host_in, C * 4, C * 4, (size_t)ctx->cfg.p, hipMemcpyHostToDevice));
+        HIP_TRY(ctx, softmax_refresh_shadow(ctx->theta, ctx->wbt, (int)ctx->cfg.p, d, nullptr));
+        HIP_TRY(ctx, hipDeviceSynchronize());
+        return BMGD_OK;
+    }
     HIP_TRY(ctx, hipMemcpy(ctx->theta, host_in, (size_t)len * 4, hipMemcpyHostToDevice));
     return BMGD_OK;
 }

@@ -75,4 +75,39 @@ hipError_t glm_launch_chain(const GlmLaunchShape& shape, const GlmArgs& args, hi
 // Step-per-launch variant: partial sums for step `args.single_step`, then reduce + update.
 hipError_t glm_launch_step(const GlmLaunchShape& shape, const GlmArgs& args, int nb, hipStream_t stream);
 
+// ---------------------------------------------------------------------------------------------------
+// Softmax regression (bf16 predictors, fp32 master weights) on the matrix cores.
+
+struct SoftmaxDims {
+    int c_pad;          // classes padded to the tile width (padding classes get probability 0)
+    int n_pad;          // mini-batch rows padded to the K tile of the gradient contraction
+    int m_pad;          // mini-batch rows padded to the tile height of the logits
+    int p_pad;          // features padded to the tile height of the gradient
+    int splits;         // split-K factor of the logits contraction
+    int k_per_split;
+};
+
+struct SoftmaxStep {
+    const void* X;          // slot, bf16 [rows][p]
+    const int32_t* y;       // class ids [rows]
+    const int32_t* idx;     // the mini-batch: nb entries of the partition
+    const void* XT;         // bf16 [p][n_pad]: this mini-batch transposed
+    float* W;               // fp32 master [p][c_pad]
+    void* WbT;              // bf16 copy, transposed [c_pad][p_pad]
+    float* U;               // logits scratch [splits][m_pad][c_pad]
+    void* Rt;               // residual scratch, bf16 [c_pad][n_pad]
+    int nb, p, C;
+    float alpha;
+};
+
+SoftmaxDims softmax_dims(int64_t p, int64_t n, int64_t C);
+hipError_t softmax_prepare(const SoftmaxDims& d);
+// XT[m][c][j] = X[perm[m n + j]][c] for every mini-batch m of one pass.
+hipError_t softmax_permute_transpose(const void* X, const int32_t* perm, void* XT, int rows, int p, int n,
+                                     const SoftmaxDims& d, hipStream_t stream);
+// One mini-batch update: logits, residual, gradient + update (three launches in stream order).
+hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t stream);
+// WbT <- bf16(W) transposed, whole matrix.
+hipError_t softmax_refresh_shadow(const float* W, void* WbT, int p, const SoftmaxDims& d, hipStream_t stream);
+
 }  // namespace bmgd

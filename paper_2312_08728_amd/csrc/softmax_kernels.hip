@@ -1,0 +1,374 @@
+// Softmax regression step on the matrix cores (bf16 inputs, fp32 accumulation and master weights).
+//
+// One mini-batch update of eq. (2.1) for the C-class member of the GLM family of Section 3.2.3:
+//     U = X_b W            (n_b x C logits)                       -- MFMA, bf16 x bf16 -> fp32
+//     R = softmax_rows(U) - onehot(y)                             -- fp32, stored as bf16
+//     W <- W - (alpha / n_b) X_b' R                               -- MFMA, fused with the update
+// with W kept in fp32 (the "master") and a bf16 copy refreshed by the update's epilogue.
+//
+// Both contractions run through one "NT" tile kernel, C[m][n] = sum_k A[m][k] B[n][k], whose two operands
+// are read along their contiguous K axis.  The data is laid out so that this is always possible:
+//   logits    A = gathered rows of X (K = features),          B = WbT [C_pad][p]  (bf16 copy, transposed)
+//   gradient  A = XT [p][n_pad] (the batch, transposed once per pass, K = rows), B = Rt [C_pad][n_pad]
+// XT is written by a permute-and-transpose pass over the slot that does not depend on W, so it sits outside
+// the sequential chain.  Tiles are 128 x 128 x 32 per workgroup of four wavefronts, each wavefront owning a
+// 64 x 64 quadrant as 2 x 2 v_mfma_f32_32x32x16_bf16 tiles.
+#include "bmgd_internal.h"
+
+namespace bmgd {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int TM = 128, TN = 128, TK = 32;
+constexpr int LDS_STRIDE = 40;                     // bf16 elements per tile row in LDS (80 bytes: 16-byte aligned, spreads banks)
+
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float f)
+{
+    unsigned u = __builtin_bit_cast(unsigned, f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// XT[m][c][j] = X[perm[m * n + j]][c] for every mini-batch m of one pass (zero for j beyond the batch).
+__global__ void __launch_bounds__(256) permute_transpose_kernel(const unsigned short* __restrict__ X,
+                                                                const int* __restrict__ perm,
+                                                                unsigned short* __restrict__ XT, int rows, int p, int n,
+                                                                int n_pad, int jtiles)
+{
+    __shared__ unsigned short tile[64][66];
+    const int m = blockIdx.x / jtiles, jt = blockIdx.x % jtiles;
+    const int j0 = jt * 64, c0 = blockIdx.y * 64;
+    const int nb = min(n, rows - m * n);
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;        // 64 x 4
+    for (int r = ty; r < 64; r += 4) {
+        const int j = j0 + r;
+        unsigned short v = 0;
+        if (j < nb && c0 + tx < p) v = X[(size_t)perm[m * n + j] * p + c0 + tx];
+        tile[r][tx] = v;
+    }
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4) {
+        const int c = c0 + r, j = j0 + tx;
+        if (c < p && j < n_pad) XT[((size_t)m * p + c) * n_pad + j] = tile[tx][r];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+struct GemmArgs {
+    const unsigned short* A;    // rows of K contiguous bf16
+    const int* a_idx;           // optional gather: row m is A + a_idx[m] * a_stride
+    long long a_stride;
+    int M;                      // valid rows of A (others read as zero)
+    const unsigned short* B;
+    long long b_stride;
+    int N;                      // valid rows of B
+    int K;                      // valid K (multiple of 8)
+    int k_per_split;            // multiple of TK
+    // epilogue: logits
+    float* U;                   // [splits][m_pad][ldu]
+    int ldu, m_pad;
+    // epilogue: update
+    float* W;                   // [p][ldw] fp32 master
+    unsigned short* WbT;        // [ldw][ldwt] bf16 copy, transposed
+    int ldw, ldwt;
+    float scale;
+};
+
+template <bool UPDATE>
+__global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
+{
+    __shared__ __align__(16) unsigned short As[TM * LDS_STRIDE];
+    __shared__ __align__(16) unsigned short Bs[TN * LDS_STRIDE];
+    __shared__ __align__(16) unsigned short Ts[UPDATE ? TN * (TM + 8) : 8];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    const int kb = blockIdx.z * g.k_per_split;
+    const int ke = min(g.K, kb + g.k_per_split);
+
+    // each thread moves two 16-byte chunks of A and two of B per K tile
+    const unsigned short* a_ptr[2];
+    const unsigned short* b_ptr[2];
+    int lds_off[2], kc[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int chunk = tid + h * 256;
+        const int row = chunk >> 2;
+        kc[h] = (chunk & 3) * 8;
+        lds_off[h] = row * LDS_STRIDE + kc[h];
+        const int am = m0 + row, bn = n0 + row;
+        a_ptr[h] = nullptr;
+        if (am < g.M) a_ptr[h] = g.A + (size_t)(g.a_idx ? g.a_idx[am] : am) * g.a_stride;
+        b_ptr[h] = bn < g.N ? g.B + (size_t)bn * g.b_stride : nullptr;
+    }
+    auto fetch = [&](int k0, uint4 (&ra)[2], uint4 (&rb)[2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int k = k0 + kc[h];
+            ra[h] = (a_ptr[h] && k < ke) ? *reinterpret_cast<const uint4*>(a_ptr[h] + k) : make_uint4(0, 0, 0, 0);
+            rb[h] = (b_ptr[h] && k < ke) ? *reinterpret_cast<const uint4*>(b_ptr[h] + k) : make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int frow = lane & 31, fk = (lane >> 5) * 8;
+
+    uint4 ra[2], rb[2];
+    fetch(kb, ra, rb);
+    for (int k0 = kb; k0 < ke; k0 += TK) {
+        __syncthreads();                             // previous tile fully consumed
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            *reinterpret_cast<uint4*>(&As[lds_off[h]]) = ra[h];
+            *reinterpret_cast<uint4*>(&Bs[lds_off[h]]) = rb[h];
+        }
+        __syncthreads();
+        if (k0 + TK < ke) fetch(k0 + TK, ra, rb);    // next tile flies while this one is multiplied
+#pragma unroll
+        for (int ks = 0; ks < TK; ks += 16) {
+            bf16x8 fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[(wm + i * 32 + frow) * LDS_STRIDE + ks + fk]));
+                fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[(wn + i * 32 + frow) * LDS_STRIDE + ks + fk]));
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // accumulator layout of the 32 x 32 tile: lane holds column (lane % 32); value v is row
+    // 8 * (v / 4) + 4 * (lane / 32) + (v % 4)
+    const int ccol = lane & 31, rbase = (lane >> 5) * 4;
+    if constexpr (!UPDATE) {
+        float* U = g.U + (size_t)blockIdx.z * g.m_pad * g.ldu;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = m0 + wm + i * 32 + 8 * (v >> 2) + rbase + (v & 3);
+                    const int c = n0 + wn + j * 32 + ccol;
+                    if (r < g.m_pad && c < g.ldu) U[(size_t)r * g.ldu + c] = acc[i][j][v];
+                }
+    } else {
+        // rows are features, columns are classes: W[r][c] -= scale * acc; bf16 copy goes out transposed
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int lr = wm + i * 32 + 8 * (v >> 2) + rbase + (v & 3);
+                    const int lc = wn + j * 32 + ccol;
+                    const int r = m0 + lr, c = n0 + lc;
+                    float w = 0.f;
+                    if (r < g.M && c < g.ldw) {
+                        w = g.W[(size_t)r * g.ldw + c] - g.scale * acc[i][j][v];
+                        g.W[(size_t)r * g.ldw + c] = w;
+                    }
+                    Ts[lc * (TM + 8) + lr] = f32_to_bf16_rne(w);
+                }
+        __syncthreads();
+        // 128 class rows x 128 features: 16 chunks of 8 features per class row
+        for (int chunk = tid; chunk < TN * (TM / 8); chunk += 256) {
+            const int lc = chunk >> 4, lr = (chunk & 15) * 8;
+            const int c = n0 + lc, r = m0 + lr;
+            if (c < g.ldw && r < g.ldwt)
+                *reinterpret_cast<uint4*>(&g.WbT[(size_t)c * g.ldwt + r]) = *reinterpret_cast<const uint4*>(&Ts[lc * (TM + 8) + lr]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// R = softmax(U) - onehot(y) for 32 rows per workgroup; written transposed as Rt[c][j] (bf16).
+// U is the sum of `splits` partial logit buffers; classes >= C are padding and get probability 0.
+constexpr int SM_ROWS = 32;
+
+__global__ void __launch_bounds__(256) softmax_residual_kernel(const float* __restrict__ U, int splits, int m_pad, int ldu,
+                                                               const int* __restrict__ y, const int* __restrict__ idx,
+                                                               int nb, int n_pad, int C, unsigned short* __restrict__ Rt)
+{
+    extern __shared__ __align__(16) unsigned short rl[];      // [SM_ROWS][ldu + 2]
+    const int lds_stride = ldu + 2;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i0 = blockIdx.x * SM_ROWS;
+    for (int rr = wave; rr < SM_ROWS; rr += 4) {
+        const int i = i0 + rr;
+        unsigned short* out = rl + rr * lds_stride;
+        if (i >= nb) {                               // padding rows of the K axis of the gradient contraction
+            for (int c = lane; c < ldu; c += 64) out[c] = 0;
+            continue;
+        }
+        const int label = y[idx[i]];
+        float mx = -INFINITY;
+        for (int c = lane; c < C; c += 64) {
+            float u = 0.f;
+            for (int s = 0; s < splits; ++s) u += U[((size_t)s * m_pad + i) * ldu + c];
+            mx = fmaxf(mx, u);
+        }
+        for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        float sum = 0.f;
+        for (int c = lane; c < C; c += 64) {
+            float u = 0.f;
+            for (int s = 0; s < splits; ++s) u += U[((size_t)s * m_pad + i) * ldu + c];
+            sum += expf(u - mx);
+        }
+        for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+        const float inv = 1.f / sum;
+        for (int c = lane; c < ldu; c += 64) {
+            float r = 0.f;
+            if (c < C) {
+                float u = 0.f;
+                for (int s = 0; s < splits; ++s) u += U[((size_t)s * m_pad + i) * ldu + c];
+                r = expf(u - mx) * inv - (c == label ? 1.f : 0.f);
+            }
+            out[c] = f32_to_bf16_rne(r);
+        }
+    }
+    __syncthreads();
+    // transposed store: for class c, SM_ROWS consecutive j
+    for (int c = threadIdx.x; c < ldu; c += 256) {
+        unsigned short v[SM_ROWS];
+#pragma unroll
+        for (int rr = 0; rr < SM_ROWS; ++rr) v[rr] = rl[rr * lds_stride + c];
+        unsigned short* dst = Rt + (size_t)c * n_pad + i0;
+        if (i0 + SM_ROWS <= n_pad) {
+#pragma unroll
+            for (int q = 0; q < SM_ROWS / 8; ++q) {
+                uint4 w;
+                w.x = v[q * 8 + 0] | ((unsigned)v[q * 8 + 1] << 16);
+                w.y = v[q * 8 + 2] | ((unsigned)v[q * 8 + 3] << 16);
+                w.z = v[q * 8 + 4] | ((unsigned)v[q * 8 + 5] << 16);
+                w.w = v[q * 8 + 6] | ((unsigned)v[q * 8 + 7] << 16);
+                *reinterpret_cast<uint4*>(dst + q * 8) = w;
+            }
+        } else {
+            for (int rr = 0; rr < SM_ROWS && i0 + rr < n_pad; ++rr) dst[rr] = v[rr];
+        }
+    }
+}
+
+// WbT[c][r] = bf16(W[r][c]) for the whole matrix (after bmgd_set_theta / at creation).
+__global__ void __launch_bounds__(256) shadow_kernel(const float* __restrict__ W, unsigned short* __restrict__ WbT, int p,
+                                                     int ldw, int ldwt)
+{
+    __shared__ float tile[32][33];
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
+    for (int rr = ty; rr < 32; rr += 8) {
+        const int r = r0 + rr, c = c0 + tx;
+        tile[rr][tx] = (r < p && c < ldw) ? W[(size_t)r * ldw + c] : 0.f;
+    }
+    __syncthreads();
+    for (int cc = ty; cc < 32; cc += 8) {
+        const int c = c0 + cc, r = r0 + tx;
+        if (c < ldw && r < ldwt) WbT[(size_t)c * ldwt + r] = f32_to_bf16_rne(tile[tx][cc]);
+    }
+}
+
+}  // namespace
+
+SoftmaxDims softmax_dims(int64_t p, int64_t n, int64_t C)
+{
+    SoftmaxDims d;
+    d.c_pad = (int)((C + TN - 1) / TN * TN);
+    d.n_pad = (int)((n + TK - 1) / TK * TK);
+    d.m_pad = (int)((n + TM - 1) / TM * TM);
+    d.p_pad = (int)((p + TM - 1) / TM * TM);
+    const int tiles = (d.m_pad / TM) * (d.c_pad / TN);
+    int splits = 1;
+    const int ktiles = (int)((p + TK - 1) / TK);
+    while (tiles * splits < 256 && splits < 8 && ktiles / (splits * 2) >= 8) splits *= 2;
+    d.splits = splits;
+    d.k_per_split = ((ktiles + splits - 1) / splits) * TK;
+    return d;
+}
+
+hipError_t softmax_permute_transpose(const void* X, const int32_t* perm, void* XT, int rows, int p, int n,
+                                     const SoftmaxDims& d, hipStream_t stream)
+{
+    const int M = (rows + n - 1) / n;
+    const int jtiles = (d.n_pad + 63) / 64;
+    dim3 grid((unsigned)(M * jtiles), (unsigned)((p + 63) / 64));
+    hipLaunchKernelGGL(permute_transpose_kernel, grid, dim3(256), 0, stream, static_cast<const unsigned short*>(X), perm,
+                       static_cast<unsigned short*>(XT), rows, p, n, d.n_pad, jtiles);
+    return hipGetLastError();
+}
+
+hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t stream)
+{
+    // 1. logits
+    GemmArgs g{};
+    g.A = static_cast<const unsigned short*>(s.X);
+    g.a_idx = s.idx;
+    g.a_stride = s.p;
+    g.M = s.nb;
+    g.B = static_cast<const unsigned short*>(s.WbT);
+    g.b_stride = d.p_pad;
+    g.N = d.c_pad;
+    g.K = s.p;
+    g.k_per_split = d.k_per_split;
+    g.U = s.U;
+    g.ldu = d.c_pad;
+    g.m_pad = d.m_pad;
+    const int mt = (s.nb + TM - 1) / TM;
+    hipLaunchKernelGGL(gemm_nt_kernel<false>, dim3(d.c_pad / TN, mt, d.splits), dim3(256), 0, stream, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // 2. residual
+    const size_t lds = (size_t)SM_ROWS * (d.c_pad + 2) * sizeof(unsigned short);
+    hipLaunchKernelGGL(softmax_residual_kernel, dim3(d.n_pad / SM_ROWS), dim3(256), lds, stream, s.U, d.splits, d.m_pad,
+                       d.c_pad, s.y, s.idx, s.nb, d.n_pad, s.C, static_cast<unsigned short*>(s.Rt));
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    // 3. gradient + update
+    GemmArgs h{};
+    h.A = static_cast<const unsigned short*>(s.XT);
+    h.a_idx = nullptr;
+    h.a_stride = d.n_pad;
+    h.M = s.p;
+    h.B = static_cast<const unsigned short*>(s.Rt);
+    h.b_stride = d.n_pad;
+    h.N = d.c_pad;
+    h.K = d.n_pad;
+    h.k_per_split = d.n_pad;
+    h.W = s.W;
+    h.WbT = static_cast<unsigned short*>(s.WbT);
+    h.ldw = d.c_pad;
+    h.ldwt = d.p_pad;
+    h.scale = s.alpha / (float)s.nb;
+    hipLaunchKernelGGL(gemm_nt_kernel<true>, dim3(d.c_pad / TN, d.p_pad / TM, 1), dim3(256), 0, stream, h);
+    return hipGetLastError();
+}
+
+hipError_t softmax_prepare(const SoftmaxDims& d)
+{
+    const size_t lds = (size_t)SM_ROWS * (d.c_pad + 2) * sizeof(unsigned short);
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_residual_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+}
+
+hipError_t softmax_refresh_shadow(const float* W, void* WbT, int p, const SoftmaxDims& d, hipStream_t stream)
+{
+    dim3 grid((unsigned)(d.c_pad / 32), (unsigned)(d.p_pad / 32));
+    hipLaunchKernelGGL(shadow_kernel, grid, dim3(256), 0, stream, W, static_cast<unsigned short*>(WbT), p, d.c_pad, d.p_pad);
+    return hipGetLastError();
+}
+
+}  // namespace bmgd
