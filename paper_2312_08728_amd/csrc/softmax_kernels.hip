@@ -197,71 +197,85 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
 }
 
 // ---------------------------------------------------------------------------------------------------
-// R = softmax(U) - onehot(y) for 32 rows per workgroup; written transposed as Rt[c][j] (bf16).
-// U is the sum of `splits` partial logit buffers; classes >= C are padding and get probability 0.
-constexpr int SM_ROWS = 32;
+// R = softmax(U) - onehot(y) for SM_ROWS rows per workgroup, one row per wavefront with the row's logits
+// held in registers so U is read once (lane l owns classes 4l .. 4l+3 of every block of 256); written
+// transposed as Rt[c][j] (bf16), 16 bytes per class and workgroup.  U is the sum of `splits` partial logit
+// buffers; classes >= C are padding and get probability 0.
+constexpr int SM_ROWS = 8;
+constexpr int SM_THREADS = SM_ROWS * 64;
+constexpr int SM_MAXB = 8;                         // blocks of 256 classes per row: c_pad <= 2048
 
-__global__ void __launch_bounds__(256) softmax_residual_kernel(const float* __restrict__ U, int splits, int m_pad, int ldu,
-                                                               const int* __restrict__ y, const int* __restrict__ idx,
-                                                               int nb, int n_pad, int C, unsigned short* __restrict__ Rt)
+__global__ void __launch_bounds__(SM_THREADS) softmax_residual_kernel(const float* __restrict__ U, int splits, int m_pad,
+                                                                      int ldu, const int* __restrict__ y,
+                                                                      const int* __restrict__ idx, int nb, int n_pad,
+                                                                      int C, unsigned short* __restrict__ Rt)
 {
-    extern __shared__ __align__(16) unsigned short rl[];      // [SM_ROWS][ldu + 2]
-    const int lds_stride = ldu + 2;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    extern __shared__ __align__(16) unsigned short rl[];      // [SM_ROWS][ldu + 8]
+    const int lds_stride = ldu + 8;
+    const int lane = threadIdx.x & 63, rr = threadIdx.x >> 6;
     const int i0 = blockIdx.x * SM_ROWS;
-    for (int rr = wave; rr < SM_ROWS; rr += 4) {
-        const int i = i0 + rr;
-        unsigned short* out = rl + rr * lds_stride;
-        if (i >= nb) {                               // padding rows of the K axis of the gradient contraction
-            for (int c = lane; c < ldu; c += 64) out[c] = 0;
-            continue;
-        }
+    const int i = i0 + rr;
+    unsigned short* out = rl + rr * lds_stride;
+    if (i >= nb) {                                   // padding rows of the K axis of the gradient contraction
+        for (int c = lane; c < ldu; c += 64) out[c] = 0;
+    } else {
         const int label = y[idx[i]];
+        float u[SM_MAXB][4];
         float mx = -INFINITY;
-        for (int c = lane; c < C; c += 64) {
-            float u = 0.f;
-            for (int s = 0; s < splits; ++s) u += U[((size_t)s * m_pad + i) * ldu + c];
-            mx = fmaxf(mx, u);
+#pragma unroll
+        for (int k = 0; k < SM_MAXB; ++k) {
+            const int c = 4 * lane + 256 * k;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) u[k][v] = -INFINITY;
+            if (c < ldu) {
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int sp = 0; sp < splits; ++sp) {
+                    const float4 q = *reinterpret_cast<const float4*>(U + ((size_t)sp * m_pad + i) * ldu + c);
+                    t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+                }
+                const float tv[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (c + v < C) { u[k][v] = tv[v]; mx = fmaxf(mx, tv[v]); }
+            }
         }
         for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
         float sum = 0.f;
-        for (int c = lane; c < C; c += 64) {
-            float u = 0.f;
-            for (int s = 0; s < splits; ++s) u += U[((size_t)s * m_pad + i) * ldu + c];
-            sum += expf(u - mx);
-        }
+#pragma unroll
+        for (int k = 0; k < SM_MAXB; ++k)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                u[k][v] = expf(u[k][v] - mx);        // exp(-inf) = 0 for padding classes
+                sum += u[k][v];
+            }
         for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
         const float inv = 1.f / sum;
-        for (int c = lane; c < ldu; c += 64) {
-            float r = 0.f;
-            if (c < C) {
-                float u = 0.f;
-                for (int s = 0; s < splits; ++s) u += U[((size_t)s * m_pad + i) * ldu + c];
-                r = expf(u - mx) * inv - (c == label ? 1.f : 0.f);
+#pragma unroll
+        for (int k = 0; k < SM_MAXB; ++k) {
+            const int c = 4 * lane + 256 * k;
+            if (c < ldu) {
+                unsigned short h[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) h[v] = f32_to_bf16_rne(u[k][v] * inv - (c + v == label ? 1.f : 0.f));
+                uint2 w;
+                w.x = h[0] | ((unsigned)h[1] << 16);
+                w.y = h[2] | ((unsigned)h[3] << 16);
+                *reinterpret_cast<uint2*>(out + c) = w;
             }
-            out[c] = f32_to_bf16_rne(r);
         }
     }
     __syncthreads();
-    // transposed store: for class c, SM_ROWS consecutive j
-    for (int c = threadIdx.x; c < ldu; c += 256) {
+    // transposed store: for class c, SM_ROWS consecutive j (16 bytes)
+    for (int c = threadIdx.x; c < ldu; c += SM_THREADS) {
         unsigned short v[SM_ROWS];
 #pragma unroll
-        for (int rr = 0; rr < SM_ROWS; ++rr) v[rr] = rl[rr * lds_stride + c];
-        unsigned short* dst = Rt + (size_t)c * n_pad + i0;
-        if (i0 + SM_ROWS <= n_pad) {
-#pragma unroll
-            for (int q = 0; q < SM_ROWS / 8; ++q) {
-                uint4 w;
-                w.x = v[q * 8 + 0] | ((unsigned)v[q * 8 + 1] << 16);
-                w.y = v[q * 8 + 2] | ((unsigned)v[q * 8 + 3] << 16);
-                w.z = v[q * 8 + 4] | ((unsigned)v[q * 8 + 5] << 16);
-                w.w = v[q * 8 + 6] | ((unsigned)v[q * 8 + 7] << 16);
-                *reinterpret_cast<uint4*>(dst + q * 8) = w;
-            }
-        } else {
-            for (int rr = 0; rr < SM_ROWS && i0 + rr < n_pad; ++rr) dst[rr] = v[rr];
-        }
+        for (int q = 0; q < SM_ROWS; ++q) v[q] = rl[q * lds_stride + c];
+        uint4 w;
+        w.x = v[0] | ((unsigned)v[1] << 16);
+        w.y = v[2] | ((unsigned)v[3] << 16);
+        w.z = v[4] | ((unsigned)v[5] << 16);
+        w.w = v[6] | ((unsigned)v[7] << 16);
+        *reinterpret_cast<uint4*>(Rt + (size_t)c * n_pad + i0) = w;
     }
 }
 
@@ -333,8 +347,8 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // 2. residual
-    const size_t lds = (size_t)SM_ROWS * (d.c_pad + 2) * sizeof(unsigned short);
-    hipLaunchKernelGGL(softmax_residual_kernel, dim3(d.n_pad / SM_ROWS), dim3(256), lds, stream, s.U, d.splits, d.m_pad,
+    const size_t lds = (size_t)SM_ROWS * (d.c_pad + 8) * sizeof(unsigned short);
+    hipLaunchKernelGGL(softmax_residual_kernel, dim3(d.n_pad / SM_ROWS), dim3(SM_THREADS), lds, stream, s.U, d.splits, d.m_pad,
                        d.c_pad, s.y, s.idx, s.nb, d.n_pad, s.C, static_cast<unsigned short*>(s.Rt));
     if ((e = hipGetLastError()) != hipSuccess) return e;
     // 3. gradient + update
@@ -359,7 +373,7 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
 
 hipError_t softmax_prepare(const SoftmaxDims& d)
 {
-    const size_t lds = (size_t)SM_ROWS * (d.c_pad + 2) * sizeof(unsigned short);
+    const size_t lds = (size_t)SM_ROWS * (d.c_pad + 8) * sizeof(unsigned short);
     return hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_residual_kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
