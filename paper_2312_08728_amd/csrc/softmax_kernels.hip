@@ -76,19 +76,35 @@ struct GemmArgs {
     unsigned short* WbT;        // [ldw][ldwt] bf16 copy, transposed
     int ldw, ldwt;
     float scale;
+    int tiles_m, tiles_n, splits;   // work items = splits * tiles_m * tiles_n, dealt to XCDs in contiguous runs
 };
+
+// K tiles are pipelined: up to kDepth tiles are requested ahead into registers, one tile sits in each of two
+// LDS buffers, and one is being multiplied.  A tile's arithmetic takes ~0.1 us while a trip to L2/HBM takes
+// ~1 us, so the loop would otherwise run at memory latency.
+constexpr int kDepth = 4;
 
 template <bool UPDATE>
 __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
 {
-    __shared__ __align__(16) unsigned short As[TM * LDS_STRIDE];
-    __shared__ __align__(16) unsigned short Bs[TN * LDS_STRIDE];
+    __shared__ __align__(16) unsigned short As[2][TM * LDS_STRIDE];
+    __shared__ __align__(16) unsigned short Bs[2][TN * LDS_STRIDE];
     __shared__ __align__(16) unsigned short Ts[UPDATE ? TN * (TM + 8) : 8];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
-    const int kb = blockIdx.z * g.k_per_split;
+    // Workgroups are handed to the 8 XCDs round robin, each XCD with its own L2.  Work items are ordered
+    // (split, tile row, tile column) and XCD x takes the x-th contiguous eighth, so the tiles that share
+    // rows of A and the whole of B for one K range meet in one L2.
+    const int total = g.splits * g.tiles_m * g.tiles_n;
+    const int per = (total + 7) / 8;
+    const int item = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
+    if (item >= total) return;
+    const int split = item / (g.tiles_m * g.tiles_n);
+    const int tile = item - split * (g.tiles_m * g.tiles_n);
+    const int m0 = (tile / g.tiles_n) * TM, n0 = (tile % g.tiles_n) * TN;
+    const int kb = split * g.k_per_split;
     const int ke = min(g.K, kb + g.k_per_split);
+    const int ntiles = (ke - kb + TK - 1) / TK;
 
     // each thread moves two 16-byte chunks of A and two of B per K tile
     const unsigned short* a_ptr[2];
@@ -105,7 +121,8 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
         if (am < g.M) a_ptr[h] = g.A + (size_t)(g.a_idx ? g.a_idx[am] : am) * g.a_stride;
         b_ptr[h] = bn < g.N ? g.B + (size_t)bn * g.b_stride : nullptr;
     }
-    auto fetch = [&](int k0, uint4 (&ra)[2], uint4 (&rb)[2]) {
+    auto fetch = [&](int tile_k, uint4 (&ra)[2], uint4 (&rb)[2]) {
+        const int k0 = kb + tile_k * TK;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int k = k0 + kc[h];
@@ -125,30 +142,37 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int frow = lane & 31, fk = (lane >> 5) * 8;
 
-    uint4 ra[2], rb[2];
-    fetch(kb, ra, rb);
-    for (int k0 = kb; k0 < ke; k0 += TK) {
-        __syncthreads();                             // previous tile fully consumed
+    uint4 ra[kDepth][2], rb[kDepth][2];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            *reinterpret_cast<uint4*>(&As[lds_off[h]]) = ra[h];
-            *reinterpret_cast<uint4*>(&Bs[lds_off[h]]) = rb[h];
-        }
-        __syncthreads();
-        if (k0 + TK < ke) fetch(k0 + TK, ra, rb);    // next tile flies while this one is multiplied
+    for (int d = 0; d < kDepth; ++d) fetch(d, ra[d], rb[d]);
+    for (int tb = 0; tb < ntiles; tb += kDepth) {
 #pragma unroll
-        for (int ks = 0; ks < TK; ks += 16) {
-            bf16x8 fa[2], fb[2];
+        for (int d = 0; d < kDepth; ++d) {
+            const int t = tb + d;
+            if (t < ntiles) {
+                const int buf = d & 1;               // kDepth is even, so tile t uses buffer t % 2
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[(wm + i * 32 + frow) * LDS_STRIDE + ks + fk]));
-                fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[(wn + i * 32 + frow) * LDS_STRIDE + ks + fk]));
+                for (int h = 0; h < 2; ++h) {
+                    *reinterpret_cast<uint4*>(&As[buf][lds_off[h]]) = ra[d][h];
+                    *reinterpret_cast<uint4*>(&Bs[buf][lds_off[h]]) = rb[d][h];
+                }
+                fetch(t + kDepth, ra[d], rb[d]);     // reads beyond the last tile come back as zeros
+                __syncthreads();                     // tile t visible; the other buffer was last read before this point
+#pragma unroll
+                for (int ks = 0; ks < TK; ks += 16) {
+                    bf16x8 fa[2], fb[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[buf][(wm + i * 32 + frow) * LDS_STRIDE + ks + fk]));
+                        fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[buf][(wn + i * 32 + frow) * LDS_STRIDE + ks + fk]));
+                    }
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                }
             }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
     }
 
@@ -156,7 +180,7 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
     // 8 * (v / 4) + 4 * (lane / 32) + (v % 4)
     const int ccol = lane & 31, rbase = (lane >> 5) * 4;
     if constexpr (!UPDATE) {
-        float* U = g.U + (size_t)blockIdx.z * g.m_pad * g.ldu;
+        float* U = g.U + (size_t)split * g.m_pad * g.ldu;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -342,8 +366,10 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
     g.U = s.U;
     g.ldu = d.c_pad;
     g.m_pad = d.m_pad;
-    const int mt = (s.nb + TM - 1) / TM;
-    hipLaunchKernelGGL(gemm_nt_kernel<false>, dim3(d.c_pad / TN, mt, d.splits), dim3(256), 0, stream, g);
+    g.tiles_m = (s.nb + TM - 1) / TM;
+    g.tiles_n = d.c_pad / TN;
+    g.splits = d.splits;
+    hipLaunchKernelGGL(gemm_nt_kernel<false>, dim3((g.tiles_m * g.tiles_n * g.splits + 7) / 8 * 8), dim3(256), 0, stream, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // 2. residual
@@ -367,7 +393,10 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
     h.ldw = d.c_pad;
     h.ldwt = d.p_pad;
     h.scale = s.alpha / (float)s.nb;
-    hipLaunchKernelGGL(gemm_nt_kernel<true>, dim3(d.c_pad / TN, d.p_pad / TM, 1), dim3(256), 0, stream, h);
+    h.tiles_m = d.p_pad / TM;
+    h.tiles_n = d.c_pad / TN;
+    h.splits = 1;
+    hipLaunchKernelGGL(gemm_nt_kernel<true>, dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(256), 0, stream, h);
     return hipGetLastError();
 }
 
