@@ -167,10 +167,120 @@ struct PollGuard {
     __device__ __forceinline__ void arm() { t0 = 0; misses = 0; }
 };
 
+// What the cross-workgroup sum needs to know about its caller.
+struct ExchangeCtx {
+    int G, p, pp, tid, block;
+    float* red;                 // [block] LDS scratch
+    int* s_abort;               // LDS flag
+    PollGuard* guard;
+};
+
+// Sum over workgroups, in fixed order, of the flagged words of columns [c_lo, c_hi) for `tag`; then
+// `apply(c, sum)` runs once per column.  Leaves *s_abort set if a wait ran out.
+// Thread (gs, cj) fetches column c_lo + cj of workgroups gs, gs + NG, ...: four words are requested back to
+// back and awaited together, so a thread pays one trip over the fabric per four workgroups.
+template <class F>
+__device__ __forceinline__ void gather_columns_impl(const ExchangeCtx& x, const unsigned long long* words, int c_lo,
+                                                    int c_hi, unsigned tag, F&& apply)
+{
+    constexpr int U = 4;
+    const int width = c_hi - c_lo;
+    if (width <= 0) return;
+    const int W = min(width, x.block);
+    const int NG = min(x.block / W, x.G);            // groups that have a workgroup to fetch
+    const int cj = x.tid % W, gs = x.tid / W;
+    float* red = x.red;
+    for (int cb = c_lo; cb < c_hi; cb += W) {
+        const int c = cb + cj;
+        if (gs < NG && c < c_hi) {
+            float t = 0.f;
+            bool dead = false;
+            for (int g0 = gs; g0 < x.G && !dead; g0 += NG * U) {
+                const unsigned long long* src[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) src[u] = words + (size_t)min(g0 + u * NG, x.G - 1) * x.pp + c;
+                unsigned long long w[U];
+                for (;;) {
+                    ll_load4(src, w);
+                    bool ready = true;
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        ready = ready && ((unsigned)(w[u] >> 32) == tag || g0 + u * NG >= x.G);
+                    if (ready) break;
+                    if (x.guard->expired()) { dead = true; break; }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (g0 + u * NG < x.G) t += __builtin_bit_cast(float, (unsigned)w[u]);
+            }
+            if (dead) *x.s_abort = 1;
+            red[gs * W + cj] = t;
+        }
+        __syncthreads();
+        if (*x.s_abort) return;
+        if (x.tid < W && cb + x.tid < c_hi) {
+            float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;   // fixed association, four loads in flight
+            int q = 0;
+            for (; q + 4 <= NG; q += 4) {
+                t0 += red[q * W + x.tid];
+                t1 += red[(q + 1) * W + x.tid];
+                t2 += red[(q + 2) * W + x.tid];
+                t3 += red[(q + 3) * W + x.tid];
+            }
+            for (; q < NG; ++q) t0 += red[q * W + x.tid];
+            apply(cb + x.tid, (t0 + t1) + (t2 + t3));
+        }
+        __syncthreads();
+    }
+}
+
+// Sliced reduction: workgroup j sums a 16-column-aligned slice, applies the update to it and publishes the
+// new values in kThetaCopies copies (a workgroup polls copy (its index mod kThetaCopies), so no single set
+// of words is polled by the whole grid); then everyone collects the whole updated theta into th_lds.
+// Returns true when a wait ran out.
+__device__ __forceinline__ bool sliced_update(const ExchangeCtx& x, const unsigned long long* words,
+                                              unsigned long long* thw, float* th_lds, float scale, unsigned tag)
+{
+    const int cw = ((x.p + x.G - 1) / x.G + 15) & ~15;   // slices are whole lines of 16 words
+    const int c_lo = min(x.p, (int)blockIdx.x * cw), c_hi = min(x.p, c_lo + cw);
+    const int pp = x.pp;
+    gather_columns_impl(x, words, c_lo, c_hi, tag, [&](int c, float t) {
+        const float v = th_lds[c] - scale * t;
+#pragma unroll
+        for (int r = 0; r < kThetaCopies; ++r) ll_store(thw + (size_t)r * pp + c, v, tag);
+    });
+    __syncthreads();
+    if (*x.s_abort) return true;
+    const unsigned long long* mine = thw + (size_t)(blockIdx.x % kThetaCopies) * pp;
+    bool dead = false;
+    for (int c0 = x.tid; c0 < x.p && !dead; c0 += 4 * x.block) {   // four words per trip over the fabric
+        const unsigned long long* src[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) src[u] = mine + min(c0 + u * x.block, x.p - 1);
+        unsigned long long w[4];
+        for (;;) {
+            ll_load4(src, w);
+            bool ready = true;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) ready = ready && (unsigned)(w[u] >> 32) == tag;
+            if (ready) break;
+            if (x.guard->expired()) { dead = true; break; }
+        }
+        if (dead) break;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (c0 + u * x.block < x.p) th_lds[c0 + u * x.block] = __builtin_bit_cast(float, (unsigned)w[u]);
+    }
+    if (dead) *x.s_abort = 1;
+    __syncthreads();
+    return *x.s_abort != 0;
+}
+
 template <int V, int CPL, int PF>
 struct RowGroup {
     float x[PF][CPL * V];
     float y[PF];
+    bool ok[PF];
 };
 
 // PIPE selects how row loads are scheduled against the theta chain:
@@ -191,7 +301,6 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
 
     constexpr int NW = BLOCK / 64;
     constexpr int E = CPL * V;                       // floats of a row held per lane
-    constexpr int U = 4;                             // flagged words polled together by one thread
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -248,40 +357,40 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
     auto batch_iters = [&](int s) { int t, m; split(s, t, m); return m == M - 1 ? iters_tail : iters_full; };
 
     // Row indices of group (s, it) for this lane's row slot; -1 where the slot has no row.
+    // The loads are unconditional (positions beyond the batch read its first entry, steps beyond the launch
+    // read the first step's) so that none of them waits for another; validity travels in `okn`, bit q.
+    unsigned okn = 0u;
     auto load_idx = [&](int s, int it, int (&idx)[PF]) {
-        if (s >= last) {
-#pragma unroll
-            for (int q = 0; q < PF; ++q) idx[q] = -1;
-            return;
-        }
-        const int nb = batch_rows(s), base = batch_base(s);
+        const bool live = s < last;
+        const int sc = live ? s : first;
+        const int nb = batch_rows(sc), base = batch_base(sc);
+        okn = 0u;
 #pragma unroll
         for (int q = 0; q < PF; ++q) {
             const int j = (it * PF + q) * S_total + myslot;
-            idx[q] = j < nb ? a.perm[base + j] : -1;
+            const bool ok = live && j < nb;
+            idx[q] = a.perm[base + (ok ? j : 0)];
+            okn |= ok ? (1u << q) : 0u;
         }
     };
     auto issue_rows = [&](const int (&idx)[PF], RowGroup<V, CPL, PF>& g) {
 #pragma unroll
         for (int q = 0; q < PF; ++q) {
-            const bool ok = idx[q] >= 0;
-            const float* row = a.X + (size_t)(ok ? idx[q] : 0) * p;
-            g.y[q] = ok ? a.y[idx[q]] : 0.f;
+            // Loads are unconditional (a slot without a row reads some valid row, a chunk beyond p reads chunk 0) so
+            // that they can all be in flight together; what they bring is neutralised where it is used:
+            // theta is 0 on chunks beyond p and the residual of a missing row is forced to 0.
+            const int i = idx[q];
+            const float* row = a.X + (size_t)i * p;
+            g.y[q] = a.y[i];
+            g.ok[q] = (okn >> q) & 1u;
 #pragma unroll
-            for (int k = 0; k < CPL; ++k) {
-                if (ok && col[k] < p) {
-                    load_vec<V>(row + col[k], &g.x[q][k * V]);
-                } else {
-#pragma unroll
-                    for (int v = 0; v < V; ++v) g.x[q][k * V + v] = 0.f;
-                }
-            }
+            for (int k = 0; k < CPL; ++k) load_vec<V>(row + (col[k] < p ? col[k] : 0), &g.x[q][k * V]);
         }
     };
     // Group (s, 0) into `g`, and the indices of the group that follows it into `idx`.
     auto prefetch_step = [&](int s, RowGroup<V, CPL, PF>& g, int (&idx)[PF]) {
         issue_rows(idx, g);
-        const bool in_step = 1 < batch_iters(s);
+        const bool in_step = 1 < batch_iters(min(s, last - 1));
         load_idx(in_step ? s : s + 1, in_step ? 1 : 0, idx);
     };
 
@@ -302,58 +411,9 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
 
     PollGuard guard{a.sync + 1, a.timeout_ticks, 0, 0};
 
-    // Sum over workgroups, in fixed order, of the flagged words of columns [c_lo, c_hi) for `tag`; then
-    // `apply(c, sum)` runs once per column.  Leaves s_abort set if a wait ran out.
-    // Thread (gs, cj) fetches column c_lo + cj of workgroups gs, gs + NG, ...: U words are requested back to
-    // back and awaited together, so a thread pays one trip over the fabric per U workgroups.
+    ExchangeCtx xc{G, p, pp, tid, BLOCK, red, &s_abort, &guard};
     auto gather_columns = [&](const unsigned long long* words, int c_lo, int c_hi, unsigned tag, auto&& apply) {
-        const int width = c_hi - c_lo;
-        if (width <= 0) return;
-        const int W = min(width, BLOCK);
-        const int NG = min(BLOCK / W, G);            // groups that have a workgroup to fetch
-        const int cj = tid % W, gs = tid / W;
-        for (int cb = c_lo; cb < c_hi; cb += W) {
-            const int c = cb + cj;
-            if (gs < NG && c < c_hi) {
-                float t = 0.f;
-                bool dead = false;
-                for (int g0 = gs; g0 < G && !dead; g0 += NG * U) {
-                    const unsigned long long* src[U];
-#pragma unroll
-                    for (int u = 0; u < U; ++u) src[u] = words + (size_t)min(g0 + u * NG, G - 1) * pp + c;
-                    unsigned long long w[U];
-                    for (;;) {
-                        ll_load4(src, w);
-                        bool ready = true;
-#pragma unroll
-                        for (int u = 0; u < U; ++u)
-                            ready = ready && ((unsigned)(w[u] >> 32) == tag || g0 + u * NG >= G);
-                        if (ready) break;
-                        if (guard.expired()) { dead = true; break; }
-                    }
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        if (g0 + u * NG < G) t += __builtin_bit_cast(float, (unsigned)w[u]);
-                }
-                if (dead) s_abort = 1;
-                red[gs * W + cj] = t;
-            }
-            __syncthreads();
-            if (s_abort) return;
-            if (tid < W && cb + tid < c_hi) {
-                float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;   // fixed association, four loads in flight
-                int q = 0;
-                for (; q + 4 <= NG; q += 4) {
-                    t0 += red[q * W + tid];
-                    t1 += red[(q + 1) * W + tid];
-                    t2 += red[(q + 2) * W + tid];
-                    t3 += red[(q + 3) * W + tid];
-                }
-                for (; q < NG; ++q) t0 += red[q * W + tid];
-                apply(cb + tid, (t0 + t1) + (t2 + t3));
-            }
-            __syncthreads();
-        }
+        gather_columns_impl(xc, words, c_lo, c_hi, tag, apply);
     };
 
     for (int s = first; s < last; ++s) {
@@ -389,7 +449,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
                     }
                 }
                 dot = group_sum(dot, L);
-                const float r = residual(a.model, dot, cur.y[q]);   // rows without data have x = 0
+                const float r = cur.ok[q] ? residual(a.model, dot, cur.y[q]) : 0.f;
 #pragma unroll
                 for (int e = 0; e < E; ++e) acc[e] = fmaf(r, cur.x[q][e], acc[e]);
             }
@@ -441,6 +501,10 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
             continue;
         }
 
+        // next step's rows do not depend on theta: in flight while the exchange resolves
+        if constexpr (PIPE == kPipeGroups) {
+            if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
+        }
         // publish this workgroup's sums as flagged words
         unsigned long long* words = a.ll_part + (size_t)(s & 1) * G * pp;
         for (int c = tid; c < p; c += BLOCK) {
@@ -448,41 +512,14 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
             for (int w = 0; w < NW; ++w) t += wpart[w * p + c];
             ll_store(words + (size_t)blockIdx.x * pp + c, t, tag);
         }
-        // next step's rows do not depend on theta: in flight while the exchange resolves
-        if constexpr (!AHEAD) {
+        if constexpr (PIPE == kPipeWide) {           // wide rows: sums first, they are what the others wait for
             if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
         }
         if (a.reduce_mode == kReduceRedundant) {
             gather_columns(words, 0, p, tag, [&](int c, float t) { th_lds[c] -= scale * t; });
             if (s_abort) return;
         } else {
-            const int cw = ((p + G - 1) / G + 15) & ~15;   // slices are whole lines of 16 words
-            const int c_lo = min(p, (int)blockIdx.x * cw), c_hi = min(p, c_lo + cw);
-            // The updated slice goes out in kThetaCopies copies; a workgroup polls copy (its index mod
-            // kThetaCopies), so no single set of words is polled by the whole grid.
-            unsigned long long* thw = a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp;
-            gather_columns(words, c_lo, c_hi, tag, [&](int c, float t) {
-                const float v = th_lds[c] - scale * t;
-#pragma unroll
-                for (int r = 0; r < kThetaCopies; ++r) ll_store(thw + (size_t)r * pp + c, v, tag);
-            });
-            __syncthreads();
-            if (s_abort) return;
-            const unsigned long long* mine = thw + (size_t)(blockIdx.x % kThetaCopies) * pp;
-            bool dead = false;
-            for (int c = tid; c < p; c += BLOCK) {
-                unsigned long long w;
-                for (;;) {
-                    w = ll_load(mine + c);
-                    if ((unsigned)(w >> 32) == tag) break;
-                    if (guard.expired()) { dead = true; break; }
-                }
-                if (dead) break;
-                th_lds[c] = __builtin_bit_cast(float, (unsigned)w);
-            }
-            if (dead) s_abort = 1;
-            __syncthreads();
-            if (s_abort) return;
+            if (sliced_update(xc, words, a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp, th_lds, scale, tag)) return;
         }
         if constexpr (AHEAD) advance_rows(s);
         load_theta_regs();

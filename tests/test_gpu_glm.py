@@ -60,13 +60,17 @@ def test_workgroup_counts_and_chain_modes(G, chain):
     assert rel_l2(got, want) <= TOL
 
 
-def test_sliced_reduction_small_grid():
-    w = _case(wl.LINEAR, 6000, 4096, 3000, 1024, T=1, R=1, alpha=1e-4, x_cov="identity")
-    X, y = wl.dataset(w)
-    want = oracle_run(w, X, y)
-    for G in (48, 256):
-        got, st = gpu_run(w, X, y, n_workgroups=G)
-        assert rel_l2(got, want) <= TOL, G
+def test_wide_rows_grids_and_chain_modes():
+    """p = 4096 and p = 2048 run the whole-workgroup-per-row kernel: single workgroup, sliced reduction on small
+    and full grids, and the step-per-launch mode."""
+    for p, alpha in ((4096, 1e-4), (2048, 2e-4), (1540, 2e-4)):
+        w = _case(wl.LINEAR, 6000, p, 3000, 1024, T=1, R=1, alpha=alpha, x_cov="identity")
+        X, y = wl.dataset(w)
+        want = oracle_run(w, X, y)
+        for G, chain in ((1, 1), (3, 1), (48, 1), (256, 1), (64, 2)):
+            got, st = gpu_run(w, X, y, n_workgroups=G, chain=chain)
+            assert st.n_workgroups == G and st.threads_per_group == 512
+            assert rel_l2(got, want) <= TOL, (p, G, chain)
 
 
 def test_edge_cases():
