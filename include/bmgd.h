@@ -172,6 +172,12 @@ int bmgd_get_theta(bmgd_ctx* ctx, float* host_out, int64_t len);
 /* Wait for all enqueued work, then overwrite theta (the initial value of Algorithm 1, or a checkpoint). */
 int bmgd_set_theta(bmgd_ctx* ctx, const float* host_in, int64_t len);
 
+/* Schedules (Theorem 4 lets the learning rate alpha_r and the number of passes T_r change with the iteration r;
+ * Section 4 uses stage-wise T): both take effect for buffers run after the call, need no synchronisation and
+ * leave theta and the buffer counter alone.  lr: finite, > 0; passes >= 1. */
+int bmgd_set_lr(bmgd_ctx* ctx, double lr);
+int bmgd_set_passes(bmgd_ctx* ctx, int passes);
+
 /* Set the buffer counter b (wait-free); with bmgd_set_theta this resumes a run exactly. */
 int bmgd_set_position(bmgd_ctx* ctx, int64_t buffer_counter);
 

@@ -26,7 +26,7 @@ BMGD_CHAIN_AUTO, BMGD_CHAIN_PERSISTENT, BMGD_CHAIN_LAUNCH = 0, 1, 2
 EXPORTS = [
     "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
     "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_device_buffer", "bmgd_get_theta",
-    "bmgd_set_theta", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
+    "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
     "bmgd_last_error", "bmgd_destroy",
 ]
 
@@ -70,6 +70,8 @@ def _load() -> C.CDLL:
     lib.bmgd_get_theta.argtypes, lib.bmgd_get_theta.restype = [vp, vp, i64], i32
     lib.bmgd_set_theta.argtypes, lib.bmgd_set_theta.restype = [vp, vp, i64], i32
     lib.bmgd_set_position.argtypes, lib.bmgd_set_position.restype = [vp, i64], i32
+    lib.bmgd_set_lr.argtypes, lib.bmgd_set_lr.restype = [vp, C.c_double], i32
+    lib.bmgd_set_passes.argtypes, lib.bmgd_set_passes.restype = [vp, i32], i32
     lib.bmgd_get_perm.argtypes, lib.bmgd_get_perm.restype = [vp, i64, i32, vp, i64], i32
     lib.bmgd_sync.argtypes, lib.bmgd_sync.restype = [vp], i32
     lib.bmgd_get_stats.argtypes, lib.bmgd_get_stats.restype = [vp, C.POINTER(bmgd_stats)], i32
@@ -145,6 +147,14 @@ def bmgd_get_theta(ctx, host_out, length) -> int:
 
 def bmgd_set_theta(ctx, host_in, length) -> int:
     return lib.bmgd_set_theta(ctx, _ptr(host_in), length)
+
+
+def bmgd_set_lr(ctx, lr) -> int:
+    return lib.bmgd_set_lr(ctx, lr)
+
+
+def bmgd_set_passes(ctx, passes) -> int:
+    return lib.bmgd_set_passes(ctx, passes)
 
 
 def bmgd_set_position(ctx, buffer_counter) -> int:
@@ -226,6 +236,12 @@ class Context:
     def set_theta(self, theta):
         a = np.ascontiguousarray(theta, dtype=np.float32).reshape(-1)
         self._check(bmgd_set_theta(self.h, a, a.size))
+
+    def set_lr(self, lr):
+        self._check(bmgd_set_lr(self.h, lr))
+
+    def set_passes(self, passes):
+        self._check(bmgd_set_passes(self.h, passes))
 
     def set_position(self, buffer_counter):
         self._check(bmgd_set_position(self.h, buffer_counter))

@@ -132,8 +132,7 @@ Layout make_layout(const bmgd_config& c)
         l.slot_x[s] = off; off += align_up((size_t)c.buffer_n * c.p * item);
         l.slot_y[s] = off; off += align_up((size_t)c.buffer_n * 4);
     }
-    const int np = std::min<int>(c.passes, kMaxPassesPerLaunch);
-    l.perm = off;    off += align_up((size_t)np * c.buffer_n * 4);
+    l.perm = off;    off += align_up((size_t)kMaxPassesPerLaunch * c.buffer_n * 4);   // passes may be raised later
     if (c.model == BMGD_SOFTMAX) {
         const SoftmaxDims d = softmax_dims(c.p, c.batch_n, C);
         const size_t m_max = (size_t)((c.buffer_n + c.batch_n - 1) / c.batch_n);
@@ -602,6 +601,22 @@ BMGD_API int bmgd_set_theta(bmgd_ctx* ctx, const float* host_in, int64_t len)
         return BMGD_OK;
     }
     HIP_TRY(ctx, hipMemcpy(ctx->theta, host_in, (size_t)len * 4, hipMemcpyHostToDevice));
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_set_lr(bmgd_ctx* ctx, double lr)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!(lr > 0.0) || !std::isfinite(lr)) return fail(ctx, BMGD_EINVAL, "lr must be finite and positive");
+    ctx->cfg.lr = lr;
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_set_passes(bmgd_ctx* ctx, int passes)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (passes < 1) return fail(ctx, BMGD_EINVAL, "passes must be at least 1");
+    ctx->cfg.passes = passes;
     return BMGD_OK;
 }
 

@@ -154,7 +154,7 @@ struct PollGuard {
     {
         __builtin_amdgcn_s_sleep(2);
         ++misses;
-        if ((misses & 31u) != 0u) return false;
+        if (misses > 2u && (misses & 31u) != 0u) return false;   // clock and flag: first misses, then every 32nd
         if (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return true;
         const long long now = wall_clock64();
         if (t0 == 0) t0 = now;

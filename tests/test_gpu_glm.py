@@ -128,6 +128,64 @@ def test_initial_value_and_resume():
     assert np.array_equal(fin, got)
 
 
+def test_schedules_of_learning_rate_and_passes():
+    """alpha_r and T_r changing with the iteration r (Theorem 4; stage-wise T of Section 4)."""
+    import torch
+    import paper_2312_08728_amd as B
+    from oracle import bmgd as O
+    w = _case(wl.LOGISTIC, 6000, 40, 2000, 250, T=3, R=3, alpha=0.2)
+    X, y = wl.dataset(w)
+    alphas, passes = [0.2, 0.2 / 2 ** 0.5, 0.2 / 3 ** 0.5], [3, 2, 1]
+    ref = O.BMGD(w.model, w.p, w.n, alphas[0], passes[0])
+    ctx = B.Context(w.p, w.N0, w.n, alphas[0], passes[0], model=w.model)
+    xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    s = torch.cuda.Stream()
+    for r in range(3):
+        ref.alpha, ref.T = alphas[r], passes[r]
+        ctx.set_lr(alphas[r])
+        ctx.set_passes(passes[r])
+        for k in range(3):
+            ref.run_buffer(X[k * 2000:(k + 1) * 2000], y[k * 2000:(k + 1) * 2000])
+            ctx.run_device_buffer(xd[k * 2000:(k + 1) * 2000], yd[k * 2000:(k + 1) * 2000], 2000, s)
+    got = ctx.get_theta()
+    st = ctx.stats()
+    ctx.close()
+    assert st.steps == 3 * 8 * (3 + 2 + 1)
+    assert rel_l2(got, ref.theta) <= TOL
+    assert B.bmgd_set_lr(None, 0.1) == B.BMGD_EINVAL
+
+
+def test_loader_ordering_under_overlap():
+    """Many large buffers through the two-slot loader with copies and compute overlapping on two streams must
+    give, bit for bit, what the resident path gives: a run that read a slot before its copy finished, or a copy
+    that overwrote a slot still being read, would change theta."""
+    w = _case(wl.LOGISTIC, 800_000, 200, 200_000, 4096, T=1, R=3, alpha=0.1)
+    X, y = wl.dataset(w)
+    a, sa = gpu_run(w, X, y)
+    b, _ = gpu_run(w, X, y, resident=True)
+    assert np.array_equal(a, b)
+    assert sa.h2d_bytes == 3 * (X.nbytes + y.nbytes)            # loads do not depend on the number of passes
+    assert sa.copy_ms > 0 and sa.compute_ms > 0 and sa.wait_ms >= 0
+
+
+def test_device_side_wait_is_bounded():
+    """With a 1 us limit on device-side waits some workgroup is bound to give up while it waits for the others:
+    the kernel must exit by itself, the next blocking call must report it, and the library must stay usable."""
+    import torch
+    import paper_2312_08728_amd as B
+    w = _case(wl.LINEAR, 20_000, 100, 20_000, 250, T=4, R=1, alpha=0.01)
+    X, y = wl.dataset(w)
+    xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    c = B.Context(w.p, w.N0, w.n, w.alpha, w.T, n_workgroups=64, barrier_timeout_us=1)
+    assert B.bmgd_run_device_buffer(c.h, xd, yd, w.N0, None) == B.BMGD_OK
+    out = np.zeros(w.p, dtype=np.float32)
+    assert B.bmgd_get_theta(c.h, out, w.p) == B.BMGD_EHIP
+    assert "barrier_timeout_us" in B.bmgd_last_error(c.h)
+    c.close()
+    got, _ = gpu_run(w, X, y, n_workgroups=64)                   # default limit: same shape runs to the end
+    assert rel_l2(got, oracle_run(w, X, y)) <= TOL
+
+
 def test_error_paths():
     import torch
     import paper_2312_08728_amd as B
@@ -145,4 +203,6 @@ def test_error_paths():
     out = np.zeros(9, dtype=np.float32)
     assert B.bmgd_get_theta(c.h, out, 9) == B.BMGD_EINVAL
     assert B.bmgd_get_theta(c.h, out, 8) == B.BMGD_OK
+    assert B.bmgd_set_lr(c.h, 0.0) == B.BMGD_EINVAL and B.bmgd_set_lr(c.h, float('nan')) == B.BMGD_EINVAL
+    assert B.bmgd_set_passes(c.h, 0) == B.BMGD_EINVAL
     c.close()
