@@ -32,7 +32,7 @@ TRAFFIC = {"cfg2": {"kernel_sha256": "ce1906b8f5a746d559ab3c14e251353e1866665b3d
 
 def _kernel_sha() -> str:
     h = hashlib.sha256()
-    for f in ("glm_kernels.hip", "bmgd_api.hip", "perm_kernel.hip"):
+    for f in ("glm_kernels.hip", "gram_kernels.hip", "bmgd_api.hip", "perm_kernel.hip"):
         with open(os.path.join(ROOT, "paper_2312_08728_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()
@@ -77,11 +77,11 @@ def _device_buffers(w, nbuf, from_host=None):
     return bufs
 
 
-def _time_resident(w, bufs, steps, warmup):
+def _time_resident(w, bufs, steps, warmup, chain=0):
     """Run `steps` buffers (cycling over bufs) after `warmup`; returns (seconds, stats delta, theta)."""
     import torch
     import paper_2312_08728_amd as B
-    ctx = B.Context(w.p, w.N0, w.n, w.alpha, w.T, model=w.model, n_classes=w.C, seed=w.seed, n_buffers=w.K)
+    ctx = B.Context(w.p, w.N0, w.n, w.alpha, w.T, model=w.model, n_classes=w.C, seed=w.seed, n_buffers=w.K, chain=chain)
     try:
         s = torch.cuda.Stream()
         for i in range(warmup):
@@ -109,6 +109,9 @@ def _time_resident(w, bufs, steps, warmup):
             "chain_ms": st1.chain_ms - st0.chain_ms,
             "chain_launches": st1.chain_launches - st0.chain_launches,
             "compute_ms": st1.compute_ms - st0.compute_ms,
+            "prep_ms": st1.prep_ms - st0.prep_ms,
+            "prep_launches": st1.prep_launches - st0.prep_launches,
+            "chain": st1.chain,
             "n_workgroups": st1.n_workgroups, "threads_per_group": st1.threads_per_group,
         }
         return dt, delta, theta
@@ -127,6 +130,28 @@ def _roofline(w, delta, traffic=None):
                 "frac": round(achieved / 2500.0, 5), "traffic": None,
                 "kernel": "gemm_nt_kernel (logits, gradient+update) + softmax_residual_kernel"}
     bytes_per_launch = _algorithmic_bytes_per_sample_gradient(w) * delta["sample_gradients"] / max(delta["chain_launches"], 1)
+    if delta.get("chain") == 3:
+        # Least squares in the form of eq. (3.1): the rows are read by the kernel that forms the moment matrices
+        # of the mini-batches, the updates are applied by the one-workgroup chain kernel.  One launch of each per
+        # buffer; the rate is the buffer's algorithmic bytes over the sum of the two average durations (the two
+        # kernels of consecutive buffers overlap, so the sum is the conservative denominator).
+        prep_s = delta["prep_ms"] / 1e3 / max(delta["prep_launches"], 1)
+        achieved = bytes_per_launch / (per_launch_s + prep_s) / 1e9
+        steps_per_launch = delta["minibatch_steps"] / max(delta["chain_launches"], 1)
+        q = w.p + 1
+        return {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
+                "kernel": "gram_mfma_kernel + gram_chain_kernel",
+                "avg_launch_ms": round((per_launch_s + prep_s) * 1e3, 4),
+                "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                "moments_kernel": {"avg_launch_ms": round(prep_s * 1e3, 4),
+                                   "reads_GBs": round(bytes_per_launch / prep_s / 1e9, 1),
+                                   "fp32_mfma_TFLOPs": round(delta["sample_gradients"] / max(delta["prep_launches"], 1)
+                                                             * q * q / prep_s / 1e12, 2)},
+                "chain_kernel": {"avg_launch_ms": round(per_launch_s * 1e3, 4),
+                                 "us_per_minibatch_update": round(per_launch_s * 1e6 / steps_per_launch, 4),
+                                 "moment_bytes_GBs": round(steps_per_launch * (w.p + 1) * w.p * 4 / per_launch_s / 1e9, 1),
+                                 "note": "one workgroup; bound by a single compute unit's load path"}}
     achieved = bytes_per_launch / per_launch_s / 1e9
     return {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
@@ -145,7 +170,7 @@ def _time_pipelined(w, X, y, steps):
         # "h2d_only": the same copies with next to no compute behind them (one full-batch update per buffer)
         alone = mode == "h2d_only"
         ctx = B.Context(w.p, w.N0, w.N0 if alone else w.n, w.alpha, 1 if alone else w.T, model=w.model,
-                        n_classes=w.C, seed=w.seed, n_buffers=w.K)
+                        n_classes=w.C, seed=w.seed, n_buffers=w.K, chain=(0 if w.model == wl.SOFTMAX or not alone else 1))
         try:
             cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
             torch.cuda.synchronize()
@@ -204,7 +229,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-others", action="store_true", help="skip the short cfg1/cfg3/cfg4 side measurements")
+    ap.add_argument("--no-others", action="store_true", help="skip the short side measurements of the other workloads")
+    ap.add_argument("--chain", type=int, default=0, help="BMGD_CHAIN_* for the primary workload (0 = automatic)")
     ap.add_argument("--no-h2d", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain elementwise copy of 1 GiB (5 launches): the known-size kernel that "
@@ -237,7 +263,7 @@ def main() -> int:
     steps = args.steps if args.steps is not None else w.R * w.K
     X, y = wl.dataset(w)
     bufs = _device_buffers(w, w.K, from_host=(X, y))
-    dt, delta, theta = _time_resident(w, bufs, steps, args.warmup)
+    dt, delta, theta = _time_resident(w, bufs, steps, args.warmup, args.chain)
     del bufs
     torch.cuda.empty_cache()
 
@@ -278,17 +304,21 @@ def main() -> int:
         result["h2d"] = {"buffers": nb, "h2d_gbs": round(piped["h2d_bytes"] / max(piped["copy_ms"], 1e-9) / 1e6, 2),
                          "copy_ms": round(piped["copy_ms"], 3), "compute_ms_alone": round(comp_alone, 3),
                          "pipelined_ms": round(piped["seconds"] * 1e3, 3),
+                         "h2d_alone_ms": round(h2d_alone, 3),
+                         "bound": "compute" if comp_alone > h2d_alone else "host-to-device link",
                          "frac_h2d_hidden": round(hidden, 4), "ceiling_at_this_T": round(ceiling, 4),
                          "overlap_efficiency": round(overlap_eff, 4)}
     del X, y
 
     if not args.no_others:
         others = {}
-        for name, nbuf in (("cfg1", 5), ("cfg3", 2), ("cfg4", 2), ("cfg5", 1)):
+        for name, nbuf, chain in (("cfg1", 5, 0), ("cfg2", 10, 1), ("cfg3", 2, 0), ("cfg4", 2, 0), ("cfg5", 1, 0)):
             wo = wl.CONFIGS[name]
             try:
                 ob = _device_buffers(wo, nbuf)
-                odt, od, _ = _time_resident(wo, ob, nbuf, 1)
+                odt, od, _ = _time_resident(wo, ob, nbuf, 1, chain)
+                if chain == 1:
+                    name += "_row_form"          # the same workload with the updates taken row by row (eq. (2.1))
                 rf = _roofline(wo, od)
                 others[name] = {"value": round(od["sample_gradients"] / odt, 1), "ms_per_step": round(odt * 1e3 / nbuf, 4),
                                 "us_per_minibatch_update": round(odt * 1e6 / od["minibatch_steps"], 3),

@@ -48,6 +48,11 @@ extern "C" {
 
 typedef struct bmgd_ctx bmgd_ctx;
 
+/* In BMGD_CHAIN_GRAM mode the sequential chain runs on a stream the library creates (default priority) while
+ * everything that reads the caller's buffer stays on compute_stream, so that the pre-pass over buffer k + 1
+ * overlaps the chain of buffer k.  The blocking calls listed above wait for that stream too; a caller that
+ * synchronises compute_stream by itself has waited for the reads of its buffers, not for the updates. */
+
 /* status codes */
 enum {
     BMGD_OK = 0,
@@ -77,7 +82,13 @@ enum {
 enum {
     BMGD_CHAIN_AUTO = 0,
     BMGD_CHAIN_PERSISTENT = 1,   /* one persistent kernel per buffer; workgroups exchange sums once per step */
-    BMGD_CHAIN_LAUNCH = 2        /* kernel launches per step, in stream order */
+    BMGD_CHAIN_LAUNCH = 2,       /* kernel launches per step, in stream order */
+    BMGD_CHAIN_GRAM = 3          /* least squares with p <= 128 only: the update in the form of eq. (3.1),
+                                    theta <- (I - alpha Sxx_m) theta + alpha Sxy_m.  The moment matrices of every
+                                    mini-batch of a pass are formed first, in parallel over the buffer (each row
+                                    read once), and the sequential chain then runs inside one workgroup at p^2
+                                    multiply-adds per step.  Same result as the row form up to the order of
+                                    summation.  BMGD_CHAIN_AUTO picks it when it applies and batch_n >= 2 p. */
 };
 
 typedef struct bmgd_config {
@@ -122,6 +133,9 @@ typedef struct bmgd_stats {
     double  chain_ms;          /* device time inside the chain kernels alone (events around each launch of the
                                   persistent kernel; in step-per-launch mode: around each pass-chunk of launches) */
     int64_t chain_launches;    /* number of such timed launches */
+    double  prep_ms;           /* BMGD_CHAIN_GRAM only: device time inside the kernels that form the moment matrices
+                                  (they run on the compute stream and overlap the chain of the buffer before) */
+    int64_t prep_launches;     /* number of those launches */
 } bmgd_stats;
 
 /* Fill *cfg with defaults: linear model, fp32, 1 class, seed 0, per-pass reshuffle, automatic launch
@@ -138,7 +152,8 @@ bmgd_ctx* bmgd_create(int64_t p, int64_t buffer_n, int64_t batch_n, double lr, i
  * reaches 2^23 (step indices inside one kernel launch are kept below that). */
 int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out);
 
-/* Device bytes a context with this configuration needs (two buffer slots, partitions, theta, scratch);
+/* Device bytes a context with this configuration needs (two buffer slots, partitions, theta, scratch; in
+ * BMGD_CHAIN_GRAM mode also 4 * ceil(buffer_n / batch_n) * (p + 1) * roundup(p, 4) floats of moment matrices);
  * 0 if the configuration is invalid.  Needs no GPU. */
 size_t bmgd_workspace_bytes(const bmgd_config* cfg);
 

@@ -21,7 +21,7 @@ BMGD_OK, BMGD_EINVAL, BMGD_ESTATE, BMGD_EHIP, BMGD_ENOMEM = 0, 1, 2, 3, 4
 BMGD_LINEAR, BMGD_LOGISTIC, BMGD_SOFTMAX = 0, 1, 2
 BMGD_F32, BMGD_BF16 = 0, 1
 BMGD_RESHUFFLE_PER_PASS, BMGD_RESHUFFLE_FIXED = 0, 1
-BMGD_CHAIN_AUTO, BMGD_CHAIN_PERSISTENT, BMGD_CHAIN_LAUNCH = 0, 1, 2
+BMGD_CHAIN_AUTO, BMGD_CHAIN_PERSISTENT, BMGD_CHAIN_LAUNCH, BMGD_CHAIN_GRAM = 0, 1, 2, 3
 
 EXPORTS = [
     "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
@@ -47,6 +47,7 @@ class bmgd_stats(C.Structure):
         ("h2d_bytes", C.c_int64), ("copy_ms", C.c_double), ("compute_ms", C.c_double),
         ("wait_ms", C.c_double), ("n_workgroups", C.c_int32), ("threads_per_group", C.c_int32),
         ("chain", C.c_int32), ("reserved", C.c_int32), ("chain_ms", C.c_double), ("chain_launches", C.c_int64),
+        ("prep_ms", C.c_double), ("prep_launches", C.c_int64),
     ]
 
 

@@ -25,7 +25,7 @@ constexpr int kMaxGroups = 256;                    // upper bound used to size t
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, total;
+    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, total;
 };
 
 struct Slot {
@@ -40,6 +40,7 @@ struct Slot {
 struct RunRecord {                                 // event quintet of one buffer, for the overlap statistics
     hipEvent_t copy_start = nullptr, copy_end = nullptr, ready = nullptr, start = nullptr, end = nullptr;
     bool has_copy = false;
+    bool owns_end = true;                          // false: `end` is the stop event of the run's last chain launch
 };
 
 }  // namespace
@@ -66,6 +67,17 @@ struct bmgd_ctx {
     float* u = nullptr;                            // softmax: logits scratch
     void* rt = nullptr;                            // softmax: residual scratch
     void* xt = nullptr;                            // softmax: transposed mini-batches of one pass
+    // eq. (3.1) form.  The pre-pass over the buffer (partitions, moment matrices) runs on the caller's compute
+    // stream and the one-workgroup chain on a stream of the library's own, so that the pre-pass of the next
+    // buffer overlaps the chain of this one; two sets of partitions and matrices alternate.
+    float* gram[2] = {nullptr, nullptr};
+    int32_t* gram_perm[2] = {nullptr, nullptr};
+    hipStream_t chain_stream = nullptr;
+    hipEvent_t prep_done[2] = {nullptr, nullptr};  // stop event of the moment kernel that filled set i (owned by open_prep)
+    hipEvent_t chain_done[2] = {nullptr, nullptr}; // stop event of the chain that read set i last (owned by open_chain)
+    bool chain_pending[2] = {false, false};
+    int gsel = 0;
+    double busy_until = 0;                         // ms since `base` up to which run time has been accounted
     uint32_t tag_epoch = 0;                        // tags handed out so far for flagged-word exchanges
     GlmLaunchShape shape{};
     int chain = BMGD_CHAIN_PERSISTENT;
@@ -74,6 +86,9 @@ struct bmgd_ctx {
     double copy_ms = 0, compute_ms = 0, wait_ms = 0, chain_ms = 0;
     int64_t chain_launches = 0;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> open_chain;   // events around chain launches, unsettled
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> open_prep;    // events of the moment-matrix launches, unsettled
+    double prep_ms = 0;
+    int64_t prep_launches = 0;
     hipEvent_t base = nullptr;
     std::vector<RunRecord> open_records;
     std::vector<hipEvent_t> event_pool;
@@ -104,8 +119,11 @@ bool valid_config(const bmgd_config& c, std::string* why)
     }
     if (c.reshuffle != BMGD_RESHUFFLE_PER_PASS && c.reshuffle != BMGD_RESHUFFLE_FIXED) return bad("unknown reshuffle mode");
     if (c.n_buffers < 0) return bad("n_buffers must be non-negative");
-    if (c.chain != BMGD_CHAIN_AUTO && c.chain != BMGD_CHAIN_PERSISTENT && c.chain != BMGD_CHAIN_LAUNCH)
+    if (c.chain != BMGD_CHAIN_AUTO && c.chain != BMGD_CHAIN_PERSISTENT && c.chain != BMGD_CHAIN_LAUNCH &&
+        c.chain != BMGD_CHAIN_GRAM)
         return bad("unknown chain mode");
+    if (c.chain == BMGD_CHAIN_GRAM && (c.model != BMGD_LINEAR || c.p > kGramMaxP))
+        return bad("BMGD_CHAIN_GRAM needs the linear model and p <= 128");
     if (c.n_workgroups < 0 || c.n_workgroups > kMaxGroups) return bad("n_workgroups must be in [0, 256]");
     if (c.barrier_timeout_us < 0) return bad("barrier_timeout_us must be non-negative");
     if (c.workspace != nullptr && (reinterpret_cast<uintptr_t>(c.workspace) % kAlign) != 0)
@@ -121,6 +139,8 @@ bool valid_config(const bmgd_config& c, std::string* why)
     if ((double)c.buffer_n * (double)c.p > 9.0e18 / 8) return bad("buffer too large");
     return true;
 }
+
+int resolve_chain(const bmgd_config& c);
 
 Layout make_layout(const bmgd_config& c)
 {
@@ -152,8 +172,23 @@ Layout make_layout(const bmgd_config& c)
         l.sync = off;    off += align_up(64);
         l.wbt = l.u = l.rt = l.xt = off;
     }
+    l.gram[0] = l.gram[1] = l.gram_perm = off;
+    if (resolve_chain(c) == BMGD_CHAIN_GRAM) {
+        const size_t set = align_up((size_t)kMaxPassesPerLaunch * (size_t)((c.buffer_n + c.batch_n - 1) / c.batch_n) *
+                                    gram_bytes_per_batch(c.p));
+        l.gram[0] = off; off += set;
+        l.gram[1] = off; off += set;
+        l.gram_perm = off; off += align_up((size_t)kMaxPassesPerLaunch * c.buffer_n * 4);   // second set of partitions
+    }
     l.total = off;
     return l;
+}
+
+int resolve_chain(const bmgd_config& c)
+{
+    if (c.model == BMGD_SOFTMAX) return BMGD_CHAIN_LAUNCH;
+    if (c.chain != BMGD_CHAIN_AUTO) return c.chain;
+    return gram_eligible(c.model, c.p, c.batch_n) ? BMGD_CHAIN_GRAM : BMGD_CHAIN_PERSISTENT;
 }
 
 int fail(bmgd_ctx* ctx, int code, const std::string& msg)
@@ -194,17 +229,23 @@ void give_event(bmgd_ctx* ctx, hipEvent_t e) { if (e) ctx->event_pool.push_back(
 void settle_records(bmgd_ctx* ctx)
 {
     for (RunRecord& r : ctx->open_records) {
-        float ms = 0.f, t_ready = 0.f, t_start = 0.f;
-        if (hipEventElapsedTime(&ms, r.start, r.end) == hipSuccess) ctx->compute_ms += ms;
+        float ms = 0.f, t_ready = 0.f, t_start = 0.f, t_end = 0.f;
+        const bool have_start = hipEventElapsedTime(&t_start, ctx->base, r.start) == hipSuccess;
+        if (have_start && hipEventElapsedTime(&t_end, ctx->base, r.end) == hipSuccess) {
+            // runs may overlap (the pre-pass of one with the chain of the one before): count the union
+            const double from = std::max<double>(t_start, ctx->busy_until);
+            if (t_end > from) ctx->compute_ms += t_end - from;
+            ctx->busy_until = std::max<double>(ctx->busy_until, t_end);
+        }
         if (r.has_copy) {
             if (hipEventElapsedTime(&ms, r.copy_start, r.copy_end) == hipSuccess) ctx->copy_ms += ms;
             // time the compute stream sat at "buffer not loaded yet"
-            if (hipEventElapsedTime(&t_ready, ctx->base, r.ready) == hipSuccess &&
-                hipEventElapsedTime(&t_start, ctx->base, r.start) == hipSuccess && t_start > t_ready)
+            if (hipEventElapsedTime(&t_ready, ctx->base, r.ready) == hipSuccess && have_start && t_start > t_ready)
                 ctx->wait_ms += t_start - t_ready;
         }
         give_event(ctx, r.copy_start); give_event(ctx, r.copy_end);
-        give_event(ctx, r.ready); give_event(ctx, r.start); give_event(ctx, r.end);
+        give_event(ctx, r.ready); give_event(ctx, r.start);
+        if (r.owns_end) give_event(ctx, r.end);
     }
     ctx->open_records.clear();
     for (auto& pr : ctx->open_chain) {
@@ -213,6 +254,12 @@ void settle_records(bmgd_ctx* ctx)
         give_event(ctx, pr.first); give_event(ctx, pr.second);
     }
     ctx->open_chain.clear();
+    for (auto& pr : ctx->open_prep) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) { ctx->prep_ms += ms; ctx->prep_launches += 1; }
+        give_event(ctx, pr.first); give_event(ctx, pr.second);
+    }
+    ctx->open_prep.clear();
 }
 
 int drain(bmgd_ctx* ctx)
@@ -220,6 +267,8 @@ int drain(bmgd_ctx* ctx)
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     if (ctx->used_copy) HIP_TRY(ctx, hipStreamSynchronize(ctx->last_copy));
     if (ctx->used_compute) HIP_TRY(ctx, hipStreamSynchronize(ctx->last_compute));
+    if (ctx->chain_stream) HIP_TRY(ctx, hipStreamSynchronize(ctx->chain_stream));
+    ctx->chain_pending[0] = ctx->chain_pending[1] = false;
     settle_records(ctx);
     unsigned flag = 0;
     HIP_TRY(ctx, hipMemcpy(&flag, ctx->sync + 1, sizeof flag, hipMemcpyDeviceToHost));
@@ -233,8 +282,11 @@ int drain(bmgd_ctx* ctx)
 int64_t batches_of(int64_t rows, int64_t n) { return (rows + n - 1) / n; }
 
 // Enqueue T passes over (x, y, rows) on `stream`.
-int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hipStream_t stream)
+// *end_event receives the stop event of the run's last kernel if that kernel carries one (and then runs on the
+// library's chain stream), else NULL: then the run ends with the last work enqueued on `stream`.
+int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hipStream_t stream, hipEvent_t* end_event)
 {
+    *end_event = nullptr;
     const bmgd_config& c = ctx->cfg;
     const int64_t n = std::min<int64_t>(c.batch_n, rows);
     const int64_t M = batches_of(rows, n);
@@ -246,12 +298,33 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         const int np = std::min(kMaxPassesPerLaunch, c.passes - t0);
         PermKeys keys{};
         const int nperm = fixed ? 1 : np;
-        if (!fixed || t0 == 0) {
-            for (int i = 0; i < nperm; ++i) perm_round_keys(c.seed, b, fixed ? 0u : (uint32_t)(t0 + i + 1), keys.key[i]);
-            HIP_TRY(ctx, launch_perm(ctx->perm, rows, nperm, keys, stream));
-        }
+        for (int i = 0; i < nperm; ++i) perm_round_keys(c.seed, b, fixed ? 0u : (uint32_t)(t0 + i + 1), keys.key[i]);
         hipEvent_t ev0 = take_event(ctx), ev1 = take_event(ctx);
         if (!ev0 || !ev1) return fail(ctx, BMGD_EHIP, "could not create events");
+        if (ctx->chain == BMGD_CHAIN_GRAM) {
+            const int i = ctx->gsel;
+            ctx->gsel ^= 1;
+            hipEvent_t pv0 = take_event(ctx), pv1 = take_event(ctx);
+            if (!pv0 || !pv1) return fail(ctx, BMGD_EHIP, "could not create events");
+            ctx->open_prep.emplace_back(pv0, pv1);
+            // set i is free once the chain that read it last has finished
+            if (ctx->chain_pending[i]) HIP_TRY(ctx, hipStreamWaitEvent(stream, ctx->chain_done[i], 0));
+            HIP_TRY(ctx, launch_perm(ctx->gram_perm[i], rows, nperm, keys, stream));
+            HIP_TRY(ctx, gram_launch_moments(static_cast<const float*>(x), static_cast<const float*>(y), ctx->gram_perm[i],
+                                             ctx->gram[i], (int)rows, (int)c.p, (int)n, np, fixed ? 0 : (int)rows, stream,
+                                             pv0, pv1));
+            ctx->prep_done[i] = pv1;
+            HIP_TRY(ctx, hipStreamWaitEvent(ctx->chain_stream, ctx->prep_done[i], 0));
+            // the timing events are completed by the chain's dispatch; the stop event also frees set i
+            HIP_TRY(ctx, gram_launch_chain(ctx->gram[i], ctx->theta, (int)rows, (int)c.p, (int)n, np, fixed ? 0 : (int)rows,
+                                           (float)c.lr, ctx->chain_stream, ev0, ev1));
+            ctx->chain_done[i] = ev1;                // stays valid until the records are settled, after a drain
+            ctx->chain_pending[i] = true;
+            ctx->open_chain.emplace_back(ev0, ev1);
+            *end_event = ev1;
+            continue;
+        }
+        if (!fixed || t0 == 0) HIP_TRY(ctx, launch_perm(ctx->perm, rows, nperm, keys, stream));
         if (c.model == BMGD_SOFTMAX) {
             HIP_TRY(ctx, hipEventRecord(ev0, stream));
             const SoftmaxDims d = softmax_dims(c.p, n, c.n_classes);
@@ -340,7 +413,9 @@ void destroy_ctx(bmgd_ctx* ctx)
     (void)hipSetDevice(ctx->device);
     if (ctx->used_copy) (void)hipStreamSynchronize(ctx->last_copy);
     if (ctx->used_compute) (void)hipStreamSynchronize(ctx->last_compute);
+    if (ctx->chain_stream) (void)hipStreamSynchronize(ctx->chain_stream);
     settle_records(ctx);
+    if (ctx->chain_stream) (void)hipStreamDestroy(ctx->chain_stream);
     give_event(ctx, ctx->pending_copy.copy_start);
     give_event(ctx, ctx->pending_copy.copy_end);
     for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
@@ -440,6 +515,10 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->u = reinterpret_cast<float*>(base + ctx->lay.u);
     ctx->rt = base + ctx->lay.rt;
     ctx->xt = base + ctx->lay.xt;
+    ctx->gram[0] = reinterpret_cast<float*>(base + ctx->lay.gram[0]);
+    ctx->gram[1] = reinterpret_cast<float*>(base + ctx->lay.gram[1]);
+    ctx->gram_perm[0] = ctx->perm;
+    ctx->gram_perm[1] = reinterpret_cast<int32_t*>(base + ctx->lay.gram_perm);
     CREATE_TRY(hipMemset(ctx->sync, 0, 64));
     if (cfg->model == BMGD_SOFTMAX) {
         // theta = 0 (padding classes included), bf16 copy = 0, residual scratch = 0
@@ -450,6 +529,8 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
         // flagged words start with tag 0, which no step ever waits for
         CREATE_TRY(hipMemset(ctx->ll_part, 0, ctx->lay.sync - ctx->lay.ll_part));
     }
+    // moment matrices: the padding entries of their layout are read (and multiplied by zero) but never written
+    if (ctx->lay.gram_perm > ctx->lay.gram[0]) CREATE_TRY(hipMemset(ctx->gram[0], 0, ctx->lay.gram_perm - ctx->lay.gram[0]));
     CREATE_TRY(hipEventCreate(&ctx->base));
     CREATE_TRY(hipEventRecord(ctx->base, nullptr));
 
@@ -463,7 +544,10 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
             return bail(BMGD_EINVAL);
         }
         CREATE_TRY(glm_prepare(&ctx->shape));
-        ctx->chain = cfg->chain == BMGD_CHAIN_AUTO ? BMGD_CHAIN_PERSISTENT : cfg->chain;
+        ctx->chain = resolve_chain(ctx->cfg);
+        if (ctx->chain == BMGD_CHAIN_GRAM) {
+            CREATE_TRY(hipStreamCreateWithFlags(&ctx->chain_stream, hipStreamNonBlocking));   // default priority
+        }
     }
     CREATE_TRY(hipDeviceSynchronize());
 #undef CREATE_TRY
@@ -525,12 +609,14 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
     HIP_TRY(ctx, hipEventRecord(rec.ready, s));
     HIP_TRY(ctx, hipStreamWaitEvent(s, slot.copy_done, 0));       // never read a slot that is still filling
     HIP_TRY(ctx, hipEventRecord(rec.start, s));
-    const int rc = enqueue_compute(ctx, slot.x, slot.y, slot.rows, s);
+    hipEvent_t last = nullptr;
+    const int rc = enqueue_compute(ctx, slot.x, slot.y, slot.rows, s, &last);
     ctx->last_compute = s;
     ctx->used_compute = true;
     if (rc != BMGD_OK) return rc;
-    HIP_TRY(ctx, hipEventRecord(rec.end, s));
-    HIP_TRY(ctx, hipEventRecord(slot.compute_done, s));
+    if (last) { give_event(ctx, rec.end); rec.end = last; rec.owns_end = false; }
+    else HIP_TRY(ctx, hipEventRecord(rec.end, s));
+    HIP_TRY(ctx, hipEventRecord(slot.compute_done, s));           // every kernel that reads the slot runs on s
     slot.was_read = true;
     ctx->open_records.push_back(rec);
     ctx->pending_copy = RunRecord();
@@ -553,11 +639,13 @@ BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void
     if (!rec.ready || !rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
     HIP_TRY(ctx, hipEventRecord(rec.ready, s));
     HIP_TRY(ctx, hipEventRecord(rec.start, s));
-    const int rc = enqueue_compute(ctx, dev_x, dev_y, rows, s);
+    hipEvent_t last = nullptr;
+    const int rc = enqueue_compute(ctx, dev_x, dev_y, rows, s, &last);
     ctx->last_compute = s;
     ctx->used_compute = true;
     if (rc != BMGD_OK) return rc;
-    HIP_TRY(ctx, hipEventRecord(rec.end, s));
+    if (last) { give_event(ctx, rec.end); rec.end = last; rec.owns_end = false; }
+    else HIP_TRY(ctx, hipEventRecord(rec.end, s));
     ctx->open_records.push_back(rec);
     return BMGD_OK;
 }
@@ -656,11 +744,14 @@ BMGD_API int bmgd_get_stats(bmgd_ctx* ctx, bmgd_stats* out)
     out->copy_ms = ctx->copy_ms;
     out->compute_ms = ctx->compute_ms;
     out->wait_ms = ctx->wait_ms;
-    out->n_workgroups = ctx->shape.G;
-    out->threads_per_group = ctx->shape.block;
+    const bool one_group = ctx->chain == BMGD_CHAIN_GRAM;       // the chain itself runs in a single workgroup
+    out->n_workgroups = one_group ? 1 : ctx->shape.G;
+    out->threads_per_group = one_group ? gram_chain_threads(ctx->cfg.p) : ctx->shape.block;
     out->chain = ctx->chain;
     out->chain_ms = ctx->chain_ms;
     out->chain_launches = ctx->chain_launches;
+    out->prep_ms = ctx->prep_ms;
+    out->prep_launches = ctx->prep_launches;
     return rc;
 }
 

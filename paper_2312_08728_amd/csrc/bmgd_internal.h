@@ -76,6 +76,24 @@ hipError_t glm_launch_chain(const GlmLaunchShape& shape, const GlmArgs& args, hi
 hipError_t glm_launch_step(const GlmLaunchShape& shape, const GlmArgs& args, int nb, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------------
+// Least squares in the form of eq. (3.1): per-mini-batch moment matrices, then a one-workgroup chain.
+
+constexpr int kGramMaxP = 128;
+// The automatic choice: least squares, p <= kGramMaxP and mini-batches of at least 2 p rows.
+bool gram_eligible(int model, int64_t p, int64_t n);
+// Bytes of moment matrices per mini-batch (Sxx_m and Sxy_m in the order the chain's threads read them).
+size_t gram_bytes_per_batch(int64_t p);
+// Threads of the one workgroup that runs the chain.
+int gram_chain_threads(int64_t p);
+// Moment matrices of all mini-batches of `npass` passes (partitions at perm + pass * perm_stride) into `gram`.
+// `start` and `stop` (each may be NULL) are completed by the kernel's own dispatch, here and below.
+hipError_t gram_launch_moments(const float* X, const float* y, const int32_t* perm, float* gram, int rows, int p, int n, int npass,
+                               int perm_stride, hipStream_t stream, hipEvent_t start, hipEvent_t stop);
+// The npass * ceil(rows / n) updates of theta from those matrices, in one workgroup.
+hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, int n, int npass, int perm_stride, float alpha,
+                             hipStream_t stream, hipEvent_t start, hipEvent_t stop);
+
+// ---------------------------------------------------------------------------------------------------
 // Softmax regression (bf16 predictors, fp32 master weights) on the matrix cores.
 
 struct SoftmaxDims {

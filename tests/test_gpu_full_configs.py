@@ -16,10 +16,12 @@ def test_cfg2_whole_run():
     w = wl.CONFIGS["cfg2"]
     X, y = wl.dataset(w)
     want = oracle_run(w, X, y)
-    got, st = gpu_run(w, X, y, resident=True)
-    assert st.steps == 15_000 and st.sample_gradients == 15_000_000
-    assert rel_l2(got, want) <= 1e-4
-    assert np.linalg.norm(got - wl.true_theta(w)) < 0.15      # and it has learnt the coefficients
+    for chain in (0, 1):                                       # automatic (the form of eq. (3.1)), then the row form
+        got, st = gpu_run(w, X, y, resident=True, chain=chain)
+        assert st.chain == (3 if chain == 0 else 1)
+        assert st.steps == 15_000 and st.sample_gradients == 15_000_000
+        assert rel_l2(got, want) <= 1e-4
+        assert np.linalg.norm(got - wl.true_theta(w)) < 0.15  # and it has learnt the coefficients
 
 
 def test_cfg3_two_full_buffers():

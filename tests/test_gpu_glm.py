@@ -20,10 +20,12 @@ def test_cfg1_full_run():
     w = wl.CONFIGS["cfg1"]
     X, y = wl.dataset(w)
     want = oracle_run(w, X, y)
-    got, st = gpu_run(w, X, y)
-    assert st.steps == w.steps and st.sample_gradients == w.sample_gradients
-    assert st.h2d_bytes == w.R * (X.nbytes + y.nbytes)
-    assert rel_l2(got, want) <= TOL
+    for chain in (0, 1):                                # 0: automatic (the form of eq. (3.1) here), 1: row form
+        got, st = gpu_run(w, X, y, chain=chain)
+        assert st.chain == (3 if chain == 0 else 1)
+        assert st.steps == w.steps and st.sample_gradients == w.sample_gradients
+        assert st.h2d_bytes == w.R * (X.nbytes + y.nbytes)
+        assert rel_l2(got, want) <= TOL
 
 
 # p chosen to hit every vector width / lanes-per-row / chunks-per-lane combination, with ragged batches
@@ -44,9 +46,32 @@ def test_shapes_two_buffers(model, p, N0, n):
               x_cov="identity")
     X, y = wl.dataset(w)
     want = oracle_run(w, X, y)
-    got, st = gpu_run(w, X, y)
+    got, st = gpu_run(w, X, y, chain=1)
     assert st.steps == w.steps
     assert rel_l2(got, want) <= TOL, (st.n_workgroups, st.threads_per_group)
+
+
+# least squares in the form of eq. (3.1): every lanes-per-row / planes-per-thread choice of the chain, every tile
+# count of the moment kernel in both of its splits over workgroups (many short batches: the wider split),
+# p not a multiple of 4, ragged batches, batches shorter than p, a single batch, both partition modes
+MOMENT_SHAPES = [(1, 300, 64), (3, 1000, 96), (10, 2000, 100), (20, 1500, 300), (37, 3000, 500), (50, 2500, 128),
+                 (64, 5000, 1000), (65, 2000, 130), (75, 3000, 750), (85, 2600, 512), (95, 2400, 600), (96, 2400, 200),
+                 (100, 10_000, 1000), (108, 2200, 1100), (116, 3000, 256), (127, 3000, 40), (128, 4000, 4000),
+                 (20, 5200, 20), (37, 5200, 20), (50, 5200, 20), (75, 5200, 20), (85, 5200, 20), (100, 5200, 20),
+                 (116, 5200, 20), (128, 5200, 20)]
+
+
+@pytest.mark.parametrize("p,N0,n", MOMENT_SHAPES)
+@pytest.mark.parametrize("reshuffle", [0, 1])
+def test_moment_form_shapes(p, N0, n, reshuffle):
+    from oracle import bmgd as O
+    N = 2 * N0 - 123
+    w = _case(wl.LINEAR, N, p, N0, n, T=5, R=2, alpha=0.5 / (p + 10), x_cov="identity")
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y, reshuffle=O.FIXED if reshuffle else O.PER_PASS)
+    got, st = gpu_run(w, X, y, chain=3, reshuffle=reshuffle)
+    assert st.steps == w.steps and st.chain == 3
+    assert rel_l2(got, want) <= TOL
 
 
 @pytest.mark.parametrize("G", [1, 2, 7, 64, 256])
@@ -78,8 +103,9 @@ def test_edge_cases():
         w = _case(wl.LINEAR, N, 6, N0, min(n, N0), T=3, R=2, alpha=0.05, x_cov="identity")
         X, y = wl.dataset(w)
         want = oracle_run(w, X, y)
-        got, _ = gpu_run(w, X, y)
-        assert rel_l2(got, want) <= TOL, (N, N0, n)
+        for chain in (1, 3):
+            got, _ = gpu_run(w, X, y, chain=chain)
+            assert rel_l2(got, want) <= TOL, (N, N0, n, chain)
 
 
 def test_resident_path_equals_loader_path_bitwise_and_is_reproducible():
@@ -96,8 +122,9 @@ def test_fixed_partition_mode():
     w = _case(wl.LINEAR, 3000, 20, 1000, 100, T=3, R=3, alpha=0.02)
     X, y = wl.dataset(w)
     want = oracle_run(w, X, y, reshuffle=O.FIXED)
-    got, _ = gpu_run(w, X, y, reshuffle=1)
-    assert rel_l2(got, want) <= TOL
+    for chain in (1, 3):
+        got, _ = gpu_run(w, X, y, reshuffle=1, chain=chain)
+        assert rel_l2(got, want) <= TOL
 
 
 def test_initial_value_and_resume():
@@ -176,13 +203,13 @@ def test_device_side_wait_is_bounded():
     w = _case(wl.LINEAR, 20_000, 100, 20_000, 250, T=4, R=1, alpha=0.01)
     X, y = wl.dataset(w)
     xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
-    c = B.Context(w.p, w.N0, w.n, w.alpha, w.T, n_workgroups=64, barrier_timeout_us=1)
+    c = B.Context(w.p, w.N0, w.n, w.alpha, w.T, n_workgroups=64, barrier_timeout_us=1, chain=B.BMGD_CHAIN_PERSISTENT)
     assert B.bmgd_run_device_buffer(c.h, xd, yd, w.N0, None) == B.BMGD_OK
     out = np.zeros(w.p, dtype=np.float32)
     assert B.bmgd_get_theta(c.h, out, w.p) == B.BMGD_EHIP
     assert "barrier_timeout_us" in B.bmgd_last_error(c.h)
     c.close()
-    got, _ = gpu_run(w, X, y, n_workgroups=64)                   # default limit: same shape runs to the end
+    got, _ = gpu_run(w, X, y, n_workgroups=64, chain=1)          # default limit: same shape runs to the end
     assert rel_l2(got, oracle_run(w, X, y)) <= TOL
 
 
