@@ -232,6 +232,9 @@ def main() -> int:
     ap.add_argument("--no-others", action="store_true", help="skip the short side measurements of the other workloads")
     ap.add_argument("--chain", type=int, default=0, help="BMGD_CHAIN_* for the primary workload (0 = automatic)")
     ap.add_argument("--no-h2d", action="store_true")
+    ap.add_argument("--device-data", action="store_true",
+                    help="draw the workload's buffers on the device (same shapes and distributions) instead of copying the "
+                         "seeded host dataset: for profiling the large workloads; implies no oracle comparison and no h2d")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain elementwise copy of 1 GiB (5 launches): the known-size kernel that "
                          "hardware-counter readings of HBM traffic are scaled by")
@@ -261,8 +264,13 @@ def main() -> int:
 
     w = wl.CONFIGS[args.workload]
     steps = args.steps if args.steps is not None else w.R * w.K
-    X, y = wl.dataset(w)
-    bufs = _device_buffers(w, w.K, from_host=(X, y))
+    if args.device_data:
+        args.no_cpu_baseline = args.no_h2d = True
+        X = y = None
+        bufs = _device_buffers(w, min(w.K, 2))
+    else:
+        X, y = wl.dataset(w)
+        bufs = _device_buffers(w, w.K, from_host=(X, y))
     dt, delta, theta = _time_resident(w, bufs, steps, args.warmup, args.chain)
     del bufs
     torch.cuda.empty_cache()
@@ -276,7 +284,8 @@ def main() -> int:
         "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": round(dt * 1e3 / steps, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.x_dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype": "bf16" if w.x_dtype == "bf16" else "f32",
+        "data": "synthetic, drawn on the device" if args.device_data else "synthetic",
         "config": {"workload": f"{w.name}: {wl.MODEL_NAMES[w.model]} regression N={w.N} p={w.p} buffer={w.N0} "
                                f"batch={w.n} passes={w.T} lr={w.alpha} (a step = one buffer = {w.T * w.M} mini-batch updates)",
                    "minibatch_updates_timed": delta["minibatch_steps"],
