@@ -106,10 +106,13 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
     const int ke = min(g.K, kb + g.k_per_split);
     const int ntiles = (ke - kb + TK - 1) / TK;
 
-    // each thread moves two 16-byte chunks of A and two of B per K tile
+    // Each thread moves two 16-byte chunks of A and two of B per K tile.  Every request is unconditional, from a
+    // clamped row and a clamped K offset; what lies outside the operands is zeroed when the chunk goes to LDS.
+    // (A branch or a select next to the load would make the compiler wait for the load on the spot.)
     const unsigned short* a_ptr[2];
     const unsigned short* b_ptr[2];
     int lds_off[2], kc[2];
+    bool a_ok[2], b_ok[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int chunk = tid + h * 256;
@@ -117,19 +120,23 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
         kc[h] = (chunk & 3) * 8;
         lds_off[h] = row * LDS_STRIDE + kc[h];
         const int am = m0 + row, bn = n0 + row;
-        a_ptr[h] = nullptr;
-        if (am < g.M) a_ptr[h] = g.A + (size_t)(g.a_idx ? g.a_idx[am] : am) * g.a_stride;
-        b_ptr[h] = bn < g.N ? g.B + (size_t)bn * g.b_stride : nullptr;
+        a_ok[h] = am < g.M;
+        b_ok[h] = bn < g.N;
+        const int amc = min(am, g.M - 1), bnc = min(bn, g.N - 1);
+        a_ptr[h] = g.A + (size_t)(g.a_idx ? g.a_idx[amc] : amc) * g.a_stride;
+        b_ptr[h] = g.B + (size_t)bnc * g.b_stride;
     }
+    const int klast = g.K - 8;                       // K is a multiple of 8
     auto fetch = [&](int tile_k, uint4 (&ra)[2], uint4 (&rb)[2]) {
         const int k0 = kb + tile_k * TK;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const int k = k0 + kc[h];
-            ra[h] = (a_ptr[h] && k < ke) ? *reinterpret_cast<const uint4*>(a_ptr[h] + k) : make_uint4(0, 0, 0, 0);
-            rb[h] = (b_ptr[h] && k < ke) ? *reinterpret_cast<const uint4*>(b_ptr[h] + k) : make_uint4(0, 0, 0, 0);
+            const int k = min(k0 + kc[h], klast);
+            ra[h] = *reinterpret_cast<const uint4*>(a_ptr[h] + k);
+            rb[h] = *reinterpret_cast<const uint4*>(b_ptr[h] + k);
         }
     };
+    auto masked = [](uint4 v, bool ok) { return ok ? v : make_uint4(0, 0, 0, 0); };
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -142,36 +149,41 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int frow = lane & 31, fk = (lane >> 5) * 8;
 
+    // Ring of kDepth register slots.  A slot goes to LDS, and only then is requested again, so no copy of it is
+    // ever live across a request; the first requests are waited for before the loop (the compiler is free to
+    // reorder them) so that the waits inside the loop count the loop's own requests, oldest slot first.  The
+    // loop has no branch: tiles past the last one are all zeros and add nothing.
     uint4 ra[kDepth][2], rb[kDepth][2];
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) fetch(d, ra[d], rb[d]);
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
     for (int tb = 0; tb < ntiles; tb += kDepth) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
             const int t = tb + d;
-            if (t < ntiles) {
-                const int buf = d & 1;               // kDepth is even, so tile t uses buffer t % 2
+            const int buf = d & 1;                   // kDepth is even, so tile t uses buffer t % 2
+            const int k0 = kb + t * TK;
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    *reinterpret_cast<uint4*>(&As[buf][lds_off[h]]) = ra[d][h];
-                    *reinterpret_cast<uint4*>(&Bs[buf][lds_off[h]]) = rb[d][h];
+            for (int h = 0; h < 2; ++h) {
+                const bool kin = k0 + kc[h] < ke;
+                *reinterpret_cast<uint4*>(&As[buf][lds_off[h]]) = masked(ra[d][h], a_ok[h] && kin);
+                *reinterpret_cast<uint4*>(&Bs[buf][lds_off[h]]) = masked(rb[d][h], b_ok[h] && kin);
+            }
+            fetch(t + kDepth, ra[d], rb[d]);
+            __syncthreads();                         // tile t visible; the other buffer was last read before this point
+#pragma unroll
+            for (int ks = 0; ks < TK; ks += 16) {
+                bf16x8 fa[2], fb[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[buf][(wm + i * 32 + frow) * LDS_STRIDE + ks + fk]));
+                    fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[buf][(wn + i * 32 + frow) * LDS_STRIDE + ks + fk]));
                 }
-                fetch(t + kDepth, ra[d], rb[d]);     // reads beyond the last tile come back as zeros
-                __syncthreads();                     // tile t visible; the other buffer was last read before this point
 #pragma unroll
-                for (int ks = 0; ks < TK; ks += 16) {
-                    bf16x8 fa[2], fb[2];
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
-                        fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[buf][(wm + i * 32 + frow) * LDS_STRIDE + ks + fk]));
-                        fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[buf][(wn + i * 32 + frow) * LDS_STRIDE + ks + fk]));
-                    }
-#pragma unroll
-                    for (int i = 0; i < 2; ++i)
-#pragma unroll
-                        for (int j = 0; j < 2; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-                }
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
             }
         }
     }
@@ -192,9 +204,20 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
                     if (r < g.m_pad && c < g.ldu) U[(size_t)r * g.ldu + c] = acc[i][j][v];
                 }
     } else {
-        // rows are features, columns are classes: W[r][c] -= scale * acc; bf16 copy goes out transposed
+        // rows are features, columns are classes: W[r][c] -= scale * acc; bf16 copy goes out transposed.
+        // The 32 master weights of a half-quadrant are requested together, from clamped addresses and without a
+        // branch, and only then combined and stored (a branch around each load would wait for it on the spot).
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i) {
+            float wv[2][16];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = min(m0 + wm + i * 32 + 8 * (v >> 2) + rbase + (v & 3), g.M - 1);
+                    const int c = min(n0 + wn + j * 32 + ccol, g.ldw - 1);
+                    wv[j][v] = g.W[(size_t)r * g.ldw + c];
+                }
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -202,13 +225,12 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
                     const int lr = wm + i * 32 + 8 * (v >> 2) + rbase + (v & 3);
                     const int lc = wn + j * 32 + ccol;
                     const int r = m0 + lr, c = n0 + lc;
-                    float w = 0.f;
-                    if (r < g.M && c < g.ldw) {
-                        w = g.W[(size_t)r * g.ldw + c] - g.scale * acc[i][j][v];
-                        g.W[(size_t)r * g.ldw + c] = w;
-                    }
+                    const bool ok = r < g.M && c < g.ldw;
+                    const float w = ok ? wv[j][v] - g.scale * acc[i][j][v] : 0.f;
+                    if (ok) g.W[(size_t)r * g.ldw + c] = w;
                     Ts[lc * (TM + 8) + lr] = f32_to_bf16_rne(w);
                 }
+        }
         __syncthreads();
         // 128 class rows x 128 features: 16 chunks of 8 features per class row
         for (int chunk = tid; chunk < TN * (TM / 8); chunk += 256) {
@@ -229,10 +251,13 @@ constexpr int SM_ROWS = 8;
 constexpr int SM_THREADS = SM_ROWS * 64;
 constexpr int SM_MAXB = 8;                         // blocks of 256 classes per row: c_pad <= 2048
 
-__global__ void __launch_bounds__(SM_THREADS) softmax_residual_kernel(const float* __restrict__ U, int splits, int m_pad,
-                                                                      int ldu, const int* __restrict__ y,
-                                                                      const int* __restrict__ idx, int nb, int n_pad,
-                                                                      int C, unsigned short* __restrict__ Rt)
+// KB = blocks of 256 classes a row spans (rounded up to a power of two), SPLITS = partial logit buffers: both
+// compile-time so that every load of a row is issued up front, unconditionally and from clamped addresses
+// (a branch or a loop around the loads would turn them into SPLITS * KB round trips to memory, one after another).
+template <int KB, int SPLITS>
+__global__ void __launch_bounds__(SM_THREADS) softmax_residual_kernel(const float* __restrict__ U, int m_pad, int ldu,
+                                                                      const int* __restrict__ y, const int* __restrict__ idx,
+                                                                      int nb, int n_pad, int C, unsigned short* __restrict__ Rt)
 {
     extern __shared__ __align__(16) unsigned short rl[];      // [SM_ROWS][ldu + 8]
     const int lds_stride = ldu + 8;
@@ -243,30 +268,33 @@ __global__ void __launch_bounds__(SM_THREADS) softmax_residual_kernel(const floa
     if (i >= nb) {                                   // padding rows of the K axis of the gradient contraction
         for (int c = lane; c < ldu; c += 64) out[c] = 0;
     } else {
-        const int label = y[idx[i]];
-        float u[SM_MAXB][4];
+        const int row = idx[i];
+        float4 q[SPLITS][KB];
+#pragma unroll
+        for (int sp = 0; sp < SPLITS; ++sp)
+#pragma unroll
+            for (int k = 0; k < KB; ++k)
+                q[sp][k] = *reinterpret_cast<const float4*>(U + ((size_t)sp * m_pad + i) * ldu + min(4 * lane + 256 * k, ldu - 4));
+        const int label = y[row];
+        float u[KB][4];
         float mx = -INFINITY;
 #pragma unroll
-        for (int k = 0; k < SM_MAXB; ++k) {
+        for (int k = 0; k < KB; ++k) {
             const int c = 4 * lane + 256 * k;
+            float4 t = q[0][k];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) u[k][v] = -INFINITY;
-            if (c < ldu) {
-                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-                for (int sp = 0; sp < splits; ++sp) {
-                    const float4 q = *reinterpret_cast<const float4*>(U + ((size_t)sp * m_pad + i) * ldu + c);
-                    t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
-                }
-                const float tv[4] = {t.x, t.y, t.z, t.w};
+            for (int sp = 1; sp < SPLITS; ++sp) { t.x += q[sp][k].x; t.y += q[sp][k].y; t.z += q[sp][k].z; t.w += q[sp][k].w; }
+            const float tv[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (c + v < C) { u[k][v] = tv[v]; mx = fmaxf(mx, tv[v]); }
+            for (int v = 0; v < 4; ++v) {
+                u[k][v] = c + v < C ? tv[v] : -INFINITY;      // padding classes (and clamped reads) count as -inf
+                mx = fmaxf(mx, u[k][v]);
             }
         }
         for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
         float sum = 0.f;
 #pragma unroll
-        for (int k = 0; k < SM_MAXB; ++k)
+        for (int k = 0; k < KB; ++k)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 u[k][v] = expf(u[k][v] - mx);        // exp(-inf) = 0 for padding classes
@@ -275,7 +303,7 @@ __global__ void __launch_bounds__(SM_THREADS) softmax_residual_kernel(const floa
         for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
         const float inv = 1.f / sum;
 #pragma unroll
-        for (int k = 0; k < SM_MAXB; ++k) {
+        for (int k = 0; k < KB; ++k) {
             const int c = 4 * lane + 256 * k;
             if (c < ldu) {
                 unsigned short h[4];
@@ -350,6 +378,39 @@ hipError_t softmax_permute_transpose(const void* X, const int32_t* perm, void* X
     return hipGetLastError();
 }
 
+namespace {
+
+template <int KB, int SPLITS>
+hipError_t launch_residual_ks(const SoftmaxDims& d, size_t lds, hipStream_t stream, const SoftmaxStep& s)
+{
+    hipLaunchKernelGGL((softmax_residual_kernel<KB, SPLITS>), dim3(d.n_pad / SM_ROWS), dim3(SM_THREADS), lds, stream, s.U, d.m_pad,
+                       d.c_pad, s.y, s.idx, s.nb, d.n_pad, s.C, static_cast<unsigned short*>(s.Rt));
+    return hipGetLastError();
+}
+
+template <int KB>
+hipError_t launch_residual_k(const SoftmaxDims& d, size_t lds, hipStream_t stream, const SoftmaxStep& s)
+{
+    switch (d.splits) {
+    case 1: return launch_residual_ks<KB, 1>(d, lds, stream, s);
+    case 2: return launch_residual_ks<KB, 2>(d, lds, stream, s);
+    case 4: return launch_residual_ks<KB, 4>(d, lds, stream, s);
+    case 8: return launch_residual_ks<KB, 8>(d, lds, stream, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_residual(const SoftmaxDims& d, size_t lds, hipStream_t stream, const SoftmaxStep& s)
+{
+    const int blocks = (d.c_pad + 255) / 256;
+    if (blocks <= 1) return launch_residual_k<1>(d, lds, stream, s);
+    if (blocks <= 2) return launch_residual_k<2>(d, lds, stream, s);
+    if (blocks <= 4) return launch_residual_k<4>(d, lds, stream, s);
+    return launch_residual_k<8>(d, lds, stream, s);
+}
+
+}  // namespace
+
 hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t stream)
 {
     // 1. logits
@@ -374,9 +435,7 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
     if (e != hipSuccess) return e;
     // 2. residual
     const size_t lds = (size_t)SM_ROWS * (d.c_pad + 8) * sizeof(unsigned short);
-    hipLaunchKernelGGL(softmax_residual_kernel, dim3(d.n_pad / SM_ROWS), dim3(SM_THREADS), lds, stream, s.U, d.splits, d.m_pad,
-                       d.c_pad, s.y, s.idx, s.nb, d.n_pad, s.C, static_cast<unsigned short*>(s.Rt));
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = launch_residual(d, lds, stream, s)) != hipSuccess) return e;
     // 3. gradient + update
     GemmArgs h{};
     h.A = static_cast<const unsigned short*>(s.XT);
@@ -402,9 +461,8 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
 
 hipError_t softmax_prepare(const SoftmaxDims& d)
 {
-    const size_t lds = (size_t)SM_ROWS * (d.c_pad + 8) * sizeof(unsigned short);
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_residual_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    // every kernel here stays within the default 64 KiB of LDS (residual kernel: 8 rows of at most 2056 bf16)
+    return d.c_pad <= 256 * SM_MAXB ? hipSuccess : hipErrorInvalidValue;
 }
 
 hipError_t softmax_refresh_shadow(const float* W, void* WbT, int p, const SoftmaxDims& d, hipStream_t stream)
