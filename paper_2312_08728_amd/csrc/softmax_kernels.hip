@@ -39,21 +39,36 @@ __global__ void __launch_bounds__(256) permute_transpose_kernel(const unsigned s
                                                                 unsigned short* __restrict__ XT, int rows, int p, int n,
                                                                 int n_pad, int jtiles)
 {
-    __shared__ unsigned short tile[64][66];
+    // 64 rows x 64 features per workgroup, moved 16 bytes at a time in both directions (p and n_pad are
+    // multiples of 8): a thread reads 8 features of one row, and writes 8 rows of one feature.
+    constexpr int TS = 72;                           // tile row stride in elements: 16-byte aligned rows
+    __shared__ __align__(16) unsigned short tile[64 * TS];
     const int m = blockIdx.x / jtiles, jt = blockIdx.x % jtiles;
     const int j0 = jt * 64, c0 = blockIdx.y * 64;
     const int nb = min(n, rows - m * n);
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;        // 64 x 4
-    for (int r = ty; r < 64; r += 4) {
-        const int j = j0 + r;
-        unsigned short v = 0;
-        if (j < nb && c0 + tx < p) v = X[(size_t)perm[m * n + j] * p + c0 + tx];
-        tile[r][tx] = v;
+    const int seg = threadIdx.x & 7, rq = threadIdx.x >> 3;      // 8 chunks x 32
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = rq + 32 * h, j = j0 + r, c = c0 + 8 * seg;
+        // unconditional load from a clamped row and chunk; zeroed below if it lies outside
+        const int row = perm[m * n + min(j, nb - 1)];
+        uint4 v = *reinterpret_cast<const uint4*>(X + (size_t)row * p + min(c, p - 8));
+        if (j >= nb || c >= p) v = make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(&tile[r * TS + 8 * seg]) = v;
     }
     __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const int c = c0 + r, j = j0 + tx;
-        if (c < p && j < n_pad) XT[((size_t)m * p + c) * n_pad + j] = tile[tx][r];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int cl = rq + 32 * h, c = c0 + cl, j = j0 + 8 * seg;
+        unsigned short e[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) e[q] = tile[(8 * seg + q) * TS + cl];
+        uint4 w;
+        w.x = e[0] | ((unsigned)e[1] << 16);
+        w.y = e[2] | ((unsigned)e[3] << 16);
+        w.z = e[4] | ((unsigned)e[5] << 16);
+        w.w = e[6] | ((unsigned)e[7] << 16);
+        if (c < p && j < n_pad) *reinterpret_cast<uint4*>(&XT[((size_t)m * p + c) * n_pad + j]) = w;
     }
 }
 
