@@ -193,6 +193,14 @@ int bmgd_set_theta(bmgd_ctx* ctx, const float* host_in, int64_t len);
 int bmgd_set_lr(bmgd_ctx* ctx, double lr);
 int bmgd_set_passes(bmgd_ctx* ctx, int passes);
 
+/* A learning rate per mini-batch update (Theorem 4 lets alpha vary over the run; Section 4.3 trains with a cosine
+ * schedule): the u-th update enqueued after this call (u = 0, 1, ...) uses host_alphas[min(u, len - 1)], whatever
+ * buffer and pass it belongs to; lr and bmgd_set_lr are ignored while a schedule is set.  len = 0 (host_alphas may
+ * then be NULL) removes the schedule.  Every value must be finite and > 0.  The table is copied: to device memory
+ * that the library allocates for it (this call is the only one besides bmgd_create* that allocates), and to the
+ * host.  Waits for all enqueued work first. */
+int bmgd_set_lr_schedule(bmgd_ctx* ctx, const float* host_alphas, int64_t len);
+
 /* Set the buffer counter b (wait-free); with bmgd_set_theta this resumes a run exactly. */
 int bmgd_set_position(bmgd_ctx* ctx, int64_t buffer_counter);
 

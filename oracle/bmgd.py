@@ -101,6 +101,21 @@ class BMGD:
         self.theta = np.zeros(shape) if theta0 is None else np.array(theta0, dtype=np.float64).reshape(shape)
         self.b = 0
         self.steps = 0
+        # Optional learning rate per mini-batch update (Theorem 4 lets alpha change over the run; Section 4.3 uses
+        # a cosine schedule): update number u, counted from the moment the schedule is set, uses
+        # lr_schedule[min(u, len - 1)]; None = the constant self.alpha.
+        self.lr_schedule = None
+        self.lr_pos = 0
+
+    def set_lr_schedule(self, alphas) -> None:
+        self.lr_schedule = None if alphas is None or len(alphas) == 0 else np.asarray(alphas, dtype=np.float64)
+        self.lr_pos = 0
+
+    def step_size(self) -> float:
+        """Learning rate of the update about to be made."""
+        if self.lr_schedule is None:
+            return self.alpha
+        return float(self.lr_schedule[min(self.lr_pos, len(self.lr_schedule) - 1)])
 
     def partition(self, N0: int, t: int) -> np.ndarray:
         """Index permutation used for pass t (1-based) of the buffer about to be processed."""
@@ -121,8 +136,9 @@ class BMGD:
                 idx = pm[start:min(start + self.n, N0)]
                 Xb = Xd[idx] if small else to_f64(X[idx])
                 g = minibatch_gradient(self.model, Xb, yd[idx], self.theta)
-                self.theta = self.theta - self.alpha * g
+                self.theta = self.theta - self.step_size() * g
                 self.steps += 1
+                self.lr_pos += 1
                 if on_step is not None:
                     on_step(self)
         self.b += 1

@@ -26,7 +26,7 @@ BMGD_CHAIN_AUTO, BMGD_CHAIN_PERSISTENT, BMGD_CHAIN_LAUNCH, BMGD_CHAIN_GRAM = 0, 
 EXPORTS = [
     "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
     "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_device_buffer", "bmgd_get_theta",
-    "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
+    "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_lr_schedule", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
     "bmgd_last_error", "bmgd_destroy",
 ]
 
@@ -72,6 +72,7 @@ def _load() -> C.CDLL:
     lib.bmgd_set_theta.argtypes, lib.bmgd_set_theta.restype = [vp, vp, i64], i32
     lib.bmgd_set_position.argtypes, lib.bmgd_set_position.restype = [vp, i64], i32
     lib.bmgd_set_lr.argtypes, lib.bmgd_set_lr.restype = [vp, C.c_double], i32
+    lib.bmgd_set_lr_schedule.argtypes, lib.bmgd_set_lr_schedule.restype = [vp, vp, C.c_int64], i32
     lib.bmgd_set_passes.argtypes, lib.bmgd_set_passes.restype = [vp, i32], i32
     lib.bmgd_get_perm.argtypes, lib.bmgd_get_perm.restype = [vp, i64, i32, vp, i64], i32
     lib.bmgd_sync.argtypes, lib.bmgd_sync.restype = [vp], i32
@@ -152,6 +153,10 @@ def bmgd_set_theta(ctx, host_in, length) -> int:
 
 def bmgd_set_lr(ctx, lr) -> int:
     return lib.bmgd_set_lr(ctx, lr)
+
+
+def bmgd_set_lr_schedule(ctx, host_alphas, length) -> int:
+    return lib.bmgd_set_lr_schedule(ctx, _ptr(host_alphas), length)
 
 
 def bmgd_set_passes(ctx, passes) -> int:
@@ -240,6 +245,10 @@ class Context:
 
     def set_lr(self, lr):
         self._check(bmgd_set_lr(self.h, lr))
+
+    def set_lr_schedule(self, alphas):
+        a = np.ascontiguousarray([] if alphas is None else alphas, dtype=np.float32).reshape(-1)
+        self._check(bmgd_set_lr_schedule(self.h, a if a.size else None, a.size))
 
     def set_passes(self, passes):
         self._check(bmgd_set_passes(self.h, passes))

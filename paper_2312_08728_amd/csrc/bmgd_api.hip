@@ -78,6 +78,11 @@ struct bmgd_ctx {
     bool chain_pending[2] = {false, false};
     int gsel = 0;
     double busy_until = 0;                         // ms since `base` up to which run time has been accounted
+    // learning rate per update (bmgd_set_lr_schedule): device copy for the kernels, host copy for the paths that
+    // pass the rate per launch; lr_pos = updates enqueued since the schedule was set
+    float* lr_tab_dev = nullptr;
+    std::vector<float> lr_tab_host;
+    int64_t lr_pos = 0;
     uint32_t tag_epoch = 0;                        // tags handed out so far for flagged-word exchanges
     GlmLaunchShape shape{};
     int chain = BMGD_CHAIN_PERSISTENT;
@@ -281,6 +286,14 @@ int drain(bmgd_ctx* ctx)
 
 int64_t batches_of(int64_t rows, int64_t n) { return (rows + n - 1) / n; }
 
+// Learning rate of the update `ahead` updates after those already enqueued.
+float rate_of(const bmgd_ctx* ctx, int64_t ahead)
+{
+    if (ctx->lr_tab_host.empty()) return (float)ctx->cfg.lr;
+    const int64_t u = std::min<int64_t>(ctx->lr_pos + ahead, (int64_t)ctx->lr_tab_host.size() - 1);
+    return ctx->lr_tab_host[(size_t)u];
+}
+
 // Enqueue T passes over (x, y, rows) on `stream`.
 // *end_event receives the stop event of the run's last kernel if that kernel carries one (and then runs on the
 // library's chain stream), else NULL: then the run ends with the last work enqueued on `stream`.
@@ -293,6 +306,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
     const bool fixed = c.reshuffle == BMGD_RESHUFFLE_FIXED;
     const uint32_t b = (uint32_t)(fixed && c.n_buffers > 0 ? ctx->buffer_counter % c.n_buffers : ctx->buffer_counter);
     const long long ticks = (c.barrier_timeout_us > 0 ? c.barrier_timeout_us : 2000000) * 100LL;
+    const int lr_len = (int)ctx->lr_tab_host.size();
 
     for (int t0 = 0; t0 < c.passes; t0 += kMaxPassesPerLaunch) {
         const int np = std::min(kMaxPassesPerLaunch, c.passes - t0);
@@ -317,7 +331,10 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
             HIP_TRY(ctx, hipStreamWaitEvent(ctx->chain_stream, ctx->prep_done[i], 0));
             // the timing events are completed by the chain's dispatch; the stop event also frees set i
             HIP_TRY(ctx, gram_launch_chain(ctx->gram[i], ctx->theta, (int)rows, (int)c.p, (int)n, np, fixed ? 0 : (int)rows,
-                                           (float)c.lr, ctx->chain_stream, ev0, ev1));
+                                           (float)c.lr, lr_len ? ctx->lr_tab_dev : nullptr,
+                                           (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0)), lr_len, ctx->chain_stream, ev0,
+                                           ev1));
+            ctx->lr_pos += (int64_t)np * M;
             ctx->chain_done[i] = ev1;                // stays valid until the records are settled, after a drain
             ctx->chain_pending[i] = true;
             ctx->open_chain.emplace_back(ev0, ev1);
@@ -345,7 +362,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
                     st.nb = (int)std::min<int64_t>(n, rows - m * n);
                     st.p = (int)c.p;
                     st.C = c.n_classes;
-                    st.alpha = (float)c.lr;
+                    st.alpha = rate_of(ctx, (int64_t)i * M + m);
                     SoftmaxDims ds = d;
                     ds.c_pad = dmax.c_pad;           // W and WbT keep the strides fixed at creation
                     ds.p_pad = dmax.p_pad;
@@ -354,6 +371,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
             }
             HIP_TRY(ctx, hipEventRecord(ev1, stream));
             ctx->open_chain.emplace_back(ev0, ev1);
+            ctx->lr_pos += (int64_t)np * M;
             continue;
         }
         GlmArgs a{};
@@ -375,6 +393,9 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         a.single_step = -1;
         a.ll_part = ctx->ll_part;
         a.ll_theta = ctx->ll_theta;
+        a.lr_tab = lr_len ? ctx->lr_tab_dev : nullptr;
+        a.lr_base = (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0));
+        a.lr_len = lr_len;
         if ((int64_t)np * M >= (int64_t(1) << 23))
             return fail(ctx, BMGD_EINVAL, "passes per launch * batches per pass must stay below 2^23; use a larger batch_n");
         HIP_TRY(ctx, hipEventRecord(ev0, stream));
@@ -393,6 +414,8 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         } else {
             for (int64_t s = 0; s < (int64_t)np * M; ++s) {
                 a.single_step = (int)s;
+                a.alpha = rate_of(ctx, s);               // this mode passes the rate per launch
+                a.lr_tab = nullptr;
                 const int64_t m = s % M;
                 const int nb = (int)std::min<int64_t>(n, rows - m * n);
                 HIP_TRY(ctx, glm_launch_step(ctx->shape, a, nb, stream));
@@ -400,6 +423,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         }
         HIP_TRY(ctx, hipEventRecord(ev1, stream));
         ctx->open_chain.emplace_back(ev0, ev1);
+        ctx->lr_pos += (int64_t)np * M;
     }
     ctx->steps += (int64_t)c.passes * M;
     ctx->sample_gradients += (int64_t)c.passes * rows;
@@ -424,6 +448,7 @@ void destroy_ctx(bmgd_ctx* ctx)
         if (s.compute_done) (void)hipEventDestroy(s.compute_done);
     }
     if (ctx->base) (void)hipEventDestroy(ctx->base);
+    if (ctx->lr_tab_dev) (void)hipFree(ctx->lr_tab_dev);
     if (ctx->owns_ws && ctx->ws) (void)hipFree(ctx->ws);
     delete ctx;
 }
@@ -697,6 +722,26 @@ BMGD_API int bmgd_set_lr(bmgd_ctx* ctx, double lr)
     if (!ctx) return BMGD_EINVAL;
     if (!(lr > 0.0) || !std::isfinite(lr)) return fail(ctx, BMGD_EINVAL, "lr must be finite and positive");
     ctx->cfg.lr = lr;
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_set_lr_schedule(bmgd_ctx* ctx, const float* host_alphas, int64_t len)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (len < 0 || len >= (int64_t(1) << 30) || (len > 0 && !host_alphas))
+        return fail(ctx, BMGD_EINVAL, "host_alphas must hold len values, 0 <= len < 2^30");
+    for (int64_t i = 0; i < len; ++i)
+        if (!(host_alphas[i] > 0.f) || !std::isfinite(host_alphas[i]))
+            return fail(ctx, BMGD_EINVAL, "every learning rate must be finite and positive");
+    const int rc = drain(ctx);
+    if (rc != BMGD_OK) return rc;
+    if (ctx->lr_tab_dev) { HIP_TRY(ctx, hipFree(ctx->lr_tab_dev)); ctx->lr_tab_dev = nullptr; }
+    ctx->lr_tab_host.clear();
+    ctx->lr_pos = 0;
+    if (len == 0) return BMGD_OK;
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->lr_tab_dev), (size_t)len * sizeof(float)));
+    HIP_TRY(ctx, hipMemcpy(ctx->lr_tab_dev, host_alphas, (size_t)len * sizeof(float), hipMemcpyHostToDevice));
+    ctx->lr_tab_host.assign(host_alphas, host_alphas + len);
     return BMGD_OK;
 }
 

@@ -64,6 +64,8 @@ struct GlmArgs {
     float alpha;
     long long timeout_ticks;
     int single_step;        // >= 0: process only that step and stop after writing partial sums
+    const float* lr_tab;    // optional learning rate per step: step s uses lr_tab[min(lr_base + s, lr_len - 1)]
+    int lr_base, lr_len;
 };
 
 // Pick V/CPL/PF/L/block/G/reduce mode for a shape; returns false if p is outside the supported range.
@@ -90,8 +92,10 @@ int gram_chain_threads(int64_t p);
 hipError_t gram_launch_moments(const float* X, const float* y, const int32_t* perm, float* gram, int rows, int p, int n, int npass,
                                int perm_stride, hipStream_t stream, hipEvent_t start, hipEvent_t stop);
 // The npass * ceil(rows / n) updates of theta from those matrices, in one workgroup.
+// lr_tab (may be NULL): learning rate of step s is lr_tab[min(lr_base + s, lr_len - 1)] instead of alpha.
 hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, int n, int npass, int perm_stride, float alpha,
-                             hipStream_t stream, hipEvent_t start, hipEvent_t stop);
+                             const float* lr_tab, int lr_base, int lr_len, hipStream_t stream, hipEvent_t start,
+                             hipEvent_t stop);
 
 // ---------------------------------------------------------------------------------------------------
 // Softmax regression (bf16 predictors, fp32 master weights) on the matrix cores.

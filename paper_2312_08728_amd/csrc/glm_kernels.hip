@@ -420,6 +420,8 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
         const int nb = batch_rows(s);
         const int iters = batch_iters(s);
         const unsigned tag = a.tag_base + (unsigned)(s - first) + 1u;
+        // requested here (a scalar load), used after the rows of the step have been processed
+        const float alpha_s = a.lr_tab ? a.lr_tab[min(a.lr_base + s, a.lr_len - 1)] : a.alpha;
         guard.arm();
         float acc[E];
 #pragma unroll
@@ -476,7 +478,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
         }
         __syncthreads();
 
-        const float scale = a.alpha / (float)nb;
+        const float scale = alpha_s / (float)nb;
         if (a.single_step >= 0) {
             // step-per-launch: plain partial sums, a second kernel reduces and updates
             float* part = a.partial + (size_t)(s & 1) * G * p;

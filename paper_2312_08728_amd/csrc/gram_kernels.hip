@@ -176,9 +176,10 @@ __global__ void __launch_bounds__(64 * kGramWaves) gram_mfma_kernel(const float*
 
 // The chain: one workgroup, theta in LDS (two copies, alternating), the matrices of the coming AHEAD steps
 // already in registers.  Thread (i, seg) = (t / TPR, t % TPR); the TPR lanes of a row add up their parts.
-template <int TPR, int KQ, int KS, int AHEAD>
+template <int TPR, int KQ, int KS, int AHEAD, bool TAB>
 __global__ void __launch_bounds__(1024) gram_chain_kernel(const float* __restrict__ gram, float* __restrict__ theta,
-                                                          GramLayout L, int nsteps, int period, float alpha)
+                                                          GramLayout L, int nsteps, int period, float alpha,
+                                                          const float* __restrict__ lr_tab, int lr_base, int lr_len)
 {
     __shared__ __align__(16) float th[2][kGramMaxP + 4 * 16];
     const int t = threadIdx.x;
@@ -189,12 +190,16 @@ __global__ void __launch_bounds__(1024) gram_chain_kernel(const float* __restric
     float4 sq[AHEAD][NQ];
     float ss[AHEAD][NS];
     float bb[AHEAD];
+    float aa[AHEAD];                                  // learning rate of the step, from the optional table
     const int ib = row_ok ? i : 0;
     int fidx = 0;                                     // matrices to request next; wraps when passes share one partition
     // Addresses are a wavefront-uniform base (scalar registers) plus a 32-bit per-thread byte offset that never
     // changes: no vector arithmetic per request.
     const unsigned off16 = (unsigned)t * 16u, off4 = (unsigned)t * 4u, offb = (unsigned)ib * 4u;
-    auto fetch = [&](float4 (&q)[NQ], float (&sc)[NS], float& bv) {
+    // TAB: the learning rate of a step comes from lr_tab (requested with the step's matrices), else it is alpha.
+    const int lr_last = lr_len - 1;
+    int lr_next = lr_base;
+    auto fetch = [&](float4 (&q)[NQ], float (&sc)[NS], float& bv, float& av) {
         const char* g = reinterpret_cast<const char*>(gram + (size_t)fidx * L.step_floats);
         fidx = fidx + 1 == period ? 0 : fidx + 1;
 #pragma unroll
@@ -202,9 +207,13 @@ __global__ void __launch_bounds__(1024) gram_chain_kernel(const float* __restric
 #pragma unroll
         for (int j = 0; j < KS; ++j) sc[j] = *reinterpret_cast<const float*>(g + (size_t)(4 * KQ + j) * L.nthr * 4 + off4);
         bv = *reinterpret_cast<const float*>(g + (size_t)L.b_off * 4 + offb);
+        if constexpr (TAB) {
+            av = lr_tab[min(lr_next, lr_last)];
+            lr_next += 1;
+        }
     };
 #pragma unroll
-    for (int d = 0; d + 1 < AHEAD; ++d) fetch(sq[d], ss[d], bb[d]);
+    for (int d = 0; d + 1 < AHEAD; ++d) fetch(sq[d], ss[d], bb[d], aa[d]);
     for (int c = t; c < kGramMaxP + 64; c += blockDim.x) { th[0][c] = c < p ? theta[c] : 0.f; th[1][c] = 0.f; }
     // The compiler is free to reorder these first requests; with all of them landed before the loop, the waits
     // it places inside the loop count only the requests of the loop itself, which are issued oldest slot first.
@@ -217,11 +226,11 @@ __global__ void __launch_bounds__(1024) gram_chain_kernel(const float* __restric
     for (int sb = 0; sb < nsteps; sb += AHEAD) {
 #pragma unroll
         for (int d = 0; d < AHEAD; ++d) {
-            const float a_eff = sb + d < nsteps ? alpha : 0.f;
+            const float a_eff = sb + d < nsteps ? (TAB ? aa[d] : alpha) : 0.f;
             // Request step s + AHEAD - 1 into the ring slot the previous step has just used up, before this step's
             // arithmetic: the memory pipeline works on the requests of all wavefronts while they compute.
             const int prev = (d + AHEAD - 1) % AHEAD;
-            fetch(sq[prev], ss[prev], bb[prev]);
+            fetch(sq[prev], ss[prev], bb[prev], aa[prev]);
             float dot0 = 0.f, dot1 = 0.f;
 #pragma unroll
             for (int k = 0; k < KQ; ++k) {
@@ -297,26 +306,30 @@ hipError_t launch_gram_mfma(bool wide, dim3 grid, size_t lds, hipStream_t stream
 }
 
 template <int TPR, int KQ, int KS>
-hipError_t launch_chain(const GramLayout& L, const float* gram, float* theta, int nsteps, int period, float alpha, hipStream_t stream,
-                        hipEvent_t start, hipEvent_t stop)
+hipError_t launch_chain(const GramLayout& L, const float* gram, float* theta, int nsteps, int period, float alpha, const float* lr_tab,
+                        int lr_base, int lr_len, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
 {
     constexpr int per_step = 4 * KQ + KS + 1;
     constexpr int AHEAD = per_step <= 9 ? 8 : per_step <= 14 ? 6 : 4;
-    hipExtLaunchKernelGGL((gram_chain_kernel<TPR, KQ, KS, AHEAD>), dim3(1), dim3(L.nthr), 0u, stream, start, stop, 0u, gram, theta, L,
-                          nsteps, period, alpha);
+    if (lr_tab)
+        hipExtLaunchKernelGGL((gram_chain_kernel<TPR, KQ, KS, AHEAD, true>), dim3(1), dim3(L.nthr), 0u, stream, start, stop, 0u, gram,
+                              theta, L, nsteps, period, alpha, lr_tab, lr_base, lr_len);
+    else
+        hipExtLaunchKernelGGL((gram_chain_kernel<TPR, KQ, KS, AHEAD, false>), dim3(1), dim3(L.nthr), 0u, stream, start, stop, 0u, gram,
+                              theta, L, nsteps, period, alpha, lr_tab, lr_base, lr_len);
     return hipGetLastError();
 }
 
 template <int TPR, int KQ>
-hipError_t launch_chain_ks(const GramLayout& L, const float* gram, float* theta, int nsteps, int period, float alpha, hipStream_t stream,
-                           hipEvent_t start, hipEvent_t stop)
+hipError_t launch_chain_ks(const GramLayout& L, const float* gram, float* theta, int nsteps, int period, float alpha,
+                           const float* lr_tab, int lr_base, int lr_len, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
 {
     switch (L.ks) {
-    case 0: return launch_chain<TPR, KQ, 0>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
-    case 1: return launch_chain<TPR, KQ, 1>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
-    case 2: return launch_chain<TPR, KQ, 2>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
-    case 3: return launch_chain<TPR, KQ, 3>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
-    case 4: return launch_chain<TPR, KQ, 4>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
+    case 0: return launch_chain<TPR, KQ, 0>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+    case 1: return launch_chain<TPR, KQ, 1>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+    case 2: return launch_chain<TPR, KQ, 2>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+    case 3: return launch_chain<TPR, KQ, 3>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+    case 4: return launch_chain<TPR, KQ, 4>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
     }
     return hipErrorInvalidValue;
 }
@@ -373,7 +386,7 @@ hipError_t gram_launch_moments(const float* X, const float* y, const int32_t* pe
 }
 
 hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, int n, int npass, int perm_stride, float alpha,
-                             hipStream_t stream, hipEvent_t start, hipEvent_t stop)
+                             const float* lr_tab, int lr_base, int lr_len, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
 {
     if (p < 1 || p > kGramMaxP) return hipErrorInvalidValue;
     const GramLayout L = make_layout(p);
@@ -381,14 +394,14 @@ hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, i
     const int nsteps = M * npass, period = perm_stride == 0 ? M : nsteps;
     if (L.tpr == 16) {
         switch (L.kq) {
-        case 0: return launch_chain_ks<16, 0>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
-        case 1: return launch_chain_ks<16, 1>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
+        case 0: return launch_chain_ks<16, 0>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+        case 1: return launch_chain_ks<16, 1>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
         }
     } else {
         switch (L.kq) {
-        case 2: return launch_chain_ks<8, 2>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
-        case 3: return launch_chain_ks<8, 3>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
-        case 4: return launch_chain_ks<8, 4>(L, gram, theta, nsteps, period, alpha, stream, start, stop);
+        case 2: return launch_chain_ks<8, 2>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+        case 3: return launch_chain_ks<8, 3>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+        case 4: return launch_chain_ks<8, 4>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
         }
     }
     return hipErrorInvalidValue;

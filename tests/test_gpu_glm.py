@@ -182,6 +182,42 @@ def test_schedules_of_learning_rate_and_passes():
     assert B.bmgd_set_lr(None, 0.1) == B.BMGD_EINVAL
 
 
+@pytest.mark.parametrize("model,p,n,chain", [(wl.LOGISTIC, 40, 250, 1), (wl.LOGISTIC, 200, 512, 1), (wl.LINEAR, 1024, 500, 1),
+                                             (wl.LINEAR, 40, 250, 3), (wl.LINEAR, 100, 300, 3), (wl.LOGISTIC, 40, 250, 2)])
+def test_learning_rate_per_update(model, p, n, chain):
+    """A cosine table of learning rates over the updates of the whole run (Section 4.3), shorter than the run so that
+    its last value has to persist, crossing passes, launches (T = 5 > 4 passes per launch) and buffers; then cleared."""
+    import torch
+    import paper_2312_08728_amd as B
+    from oracle import bmgd as O
+    w = _case(model, 6000, p, 2000, n, T=5, R=1, alpha=0.5 / (p + 10) if model == wl.LINEAR else 0.2, x_cov="identity")
+    X, y = wl.dataset(w)
+    updates = 3 * 5 * (-(-2000 // n))
+    base = w.alpha
+    table = [base * (0.1 + 0.9 * 0.5 * (1 + np.cos(np.pi * u / (updates - 20)))) for u in range(updates - 20)]
+    ref = O.BMGD(w.model, w.p, w.n, 7.0, w.T)                   # 7.0: never used while the table is set
+    ref.set_lr_schedule(np.asarray(table, dtype=np.float32))    # the library holds the table in fp32
+    ctx = B.Context(w.p, w.N0, w.n, 7.0, w.T, model=w.model, chain=chain)
+    ctx.set_lr_schedule(table)
+    xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    s = torch.cuda.Stream()
+    for k in range(3):
+        ref.run_buffer(X[k * 2000:(k + 1) * 2000], y[k * 2000:(k + 1) * 2000])
+        ctx.run_device_buffer(xd[k * 2000:(k + 1) * 2000], yd[k * 2000:(k + 1) * 2000], 2000, s)
+    got = ctx.get_theta()
+    assert ctx.stats().steps == updates
+    assert rel_l2(got, ref.theta) <= TOL
+    # cleared: the constant rate applies again
+    ref.set_lr_schedule(None); ref.alpha = base
+    ctx.set_lr_schedule(None); ctx.set_lr(base)
+    ref.run_buffer(X[:2000], y[:2000])
+    ctx.run_device_buffer(xd[:2000], yd[:2000], 2000, s)
+    assert rel_l2(ctx.get_theta(), ref.theta) <= TOL
+    assert B.bmgd_set_lr_schedule(ctx.h, np.array([0.1, -1.0], dtype=np.float32), 2) == B.BMGD_EINVAL
+    assert B.bmgd_set_lr_schedule(ctx.h, None, 3) == B.BMGD_EINVAL
+    ctx.close()
+
+
 def test_loader_ordering_under_overlap():
     """Many large buffers through the two-slot loader with copies and compute overlapping on two streams must
     give, bit for bit, what the resident path gives: a run that read a slot before its copy finished, or a copy

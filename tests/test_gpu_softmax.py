@@ -58,3 +58,24 @@ def test_softmax_argument_checks():
             setattr(cfg, k, v)
         rc, h = B.bmgd_create_ex(cfg)
         assert rc == B.BMGD_EINVAL and h is None, kw
+
+
+def test_softmax_learning_rate_per_update():
+    import torch
+    import paper_2312_08728_amd as B
+    from oracle import bmgd as O
+    w = _case(2000, 128, 40, 1000, 256, T=2, R=1)
+    X, y = wl.dataset(w)
+    table = [0.08 / (1 + 0.3 * u) for u in range(10)]            # 16 updates in the run: the last value persists
+    ref = O.BMGD(w.model, w.p, w.n, 9.0, w.T, C=w.C)
+    ref.set_lr_schedule(np.asarray(table, dtype=np.float32))
+    ctx = B.Context(w.p, w.N0, w.n, 9.0, w.T, model=w.model, n_classes=w.C, x_dtype=B.BMGD_BF16)
+    ctx.set_lr_schedule(table)
+    xd, yd = torch.from_numpy(X.view(np.int16)).cuda(), torch.from_numpy(y).cuda()
+    s = torch.cuda.Stream()
+    for k in range(2):
+        ref.run_buffer(X[k * 1000:(k + 1) * 1000], y[k * 1000:(k + 1) * 1000])
+        ctx.run_device_buffer(xd[k * 1000:(k + 1) * 1000], yd[k * 1000:(k + 1) * 1000], 1000, s)
+    got = ctx.get_theta().reshape(w.p, w.C)
+    ctx.close()
+    assert rel_l2(got, ref.theta) <= TOL

@@ -190,3 +190,45 @@ def test_ragged_last_batch_is_averaged_over_its_own_size():
     th -= 0.1 * ((x[k] * th - 1) * x[k]) / 1
     got = bmgd.run(LIN, X, y, N0=3, n=2, alpha=0.1, T=1, R=1)
     assert abs(got[0] - th) < 1e-15
+
+
+def test_per_update_learning_rates_hand_unrolled_and_special_cases():
+    """A learning rate per mini-batch update (Theorem 4; cosine schedule of Section 4.3): written out with scalars on
+    N0 = 4, p = 1, n = 2 over two buffers; the table's last value persists; a constant table is the constant rate;
+    and with full batches and rates 1/lambda on an orthogonal design one update lands on the OLS solution."""
+    x = [1.0, -2.0, 0.5, 3.0]
+    yv = [0.5, 1.0, -1.0, 2.0]
+    X = np.array(x, dtype=np.float32).reshape(4, 1)
+    y = np.array(yv, dtype=np.float32)
+    table = [0.2, 0.1, 0.05]                            # shorter than the 4 updates of the run
+    th = 0.0
+    u = 0
+    for b in (0, 1):
+        pm = P.perm_scalar(0, b, 1, 4)
+        for m in range(2):
+            i, j = pm[2 * m], pm[2 * m + 1]
+            g = ((x[i] * th - yv[i]) * x[i] + (x[j] * th - yv[j]) * x[j]) / 2
+            th -= table[min(u, 2)] * g
+            u += 1
+    st = bmgd.BMGD(LIN, 1, 2, 123.0, 1)                 # the constant rate must not be used once a table is set
+    st.set_lr_schedule(table)
+    st.run_buffer(X, y)
+    st.run_buffer(X, y)
+    assert abs(st.theta[0] - th) < 1e-15
+
+    Xd, yd, _ = _data(600, 5, seed=3)
+    a = bmgd.BMGD(LIN, 5, 100, 0.03, 2)
+    b_ = bmgd.BMGD(LIN, 5, 100, 0.5, 2)
+    b_.set_lr_schedule([0.03] * 7)
+    assert np.array_equal(a.run_buffer(Xd, yd), b_.run_buffer(Xd, yd))
+    b_.set_lr_schedule(None)                            # cleared: back to the constant rate
+    assert b_.step_size() == 0.5
+
+    # orthogonal columns with squared norms N * lam_j... use one column: a full-batch update with alpha = 1 / Sxx
+    # solves the one-dimensional least squares problem exactly
+    xc, yc = Xd[:, :1].astype(np.float64), yd.astype(np.float64)
+    sxx = float((xc[:, 0] ** 2).mean())
+    c = bmgd.BMGD(LIN, 1, 600, 1.0, 1)
+    c.set_lr_schedule([1.0 / sxx])
+    got = c.run_buffer(Xd[:, :1], yd)
+    assert abs(got[0] - float((xc[:, 0] * yc).mean()) / sxx) < 1e-12
