@@ -91,6 +91,15 @@ enum {
                                     summation.  BMGD_CHAIN_AUTO picks it when it applies and batch_n >= 2 p. */
 };
 
+/* update rule fed with the mini-batch gradient g of eq. (2.1) (Section 4.3 combines the buffering idea with NAG and
+ * Adam: "BNAG", "BAdam").  State (v; m and s) starts at zero and is carried across buffers like theta.
+ *   BMGD_OPT_SGD       theta <- theta - alpha g                                                 (Algorithm 1)
+ *   BMGD_OPT_MOMENTUM  v <- mu v - alpha g;  theta <- theta + v
+ *   BMGD_OPT_NAG       v <- mu v - alpha g;  theta <- theta + mu v - alpha g
+ *   BMGD_OPT_ADAM      m <- b1 m + (1 - b1) g;  s <- b2 s + (1 - b2) g^2;  k <- k + 1;
+ *                      theta <- theta - alpha (m / (1 - b1^k)) / (sqrt(s / (1 - b2^k)) + eps) */
+enum { BMGD_OPT_SGD = 0, BMGD_OPT_MOMENTUM = 1, BMGD_OPT_NAG = 2, BMGD_OPT_ADAM = 3 };
+
 typedef struct bmgd_config {
     int64_t  p;            /* features per row (> 0) */
     int64_t  buffer_n;     /* N0: rows a slot can hold (> 0, < 2^30) */
@@ -114,6 +123,12 @@ typedef struct bmgd_config {
                               NULL = the library allocates (and frees) it.  Must be 256-byte aligned and
                               stay valid until bmgd_destroy(). */
     size_t   workspace_bytes;
+    int32_t  optimizer;    /* BMGD_OPT_*; anything but BMGD_OPT_SGD adds one or two theta-sized state arrays */
+    int32_t  reserved;
+    double   momentum;     /* mu of MOMENTUM / NAG, in [0, 1) */
+    double   beta1;        /* Adam, in [0, 1) */
+    double   beta2;        /* Adam, in [0, 1) */
+    double   eps;          /* Adam, >= 0 */
 } bmgd_config;
 
 typedef struct bmgd_stats {
@@ -139,7 +154,8 @@ typedef struct bmgd_stats {
 } bmgd_stats;
 
 /* Fill *cfg with defaults: linear model, fp32, 1 class, seed 0, per-pass reshuffle, automatic launch
- * shape, library-owned memory.  p, buffer_n, batch_n, lr, passes are left 0 for the caller to set. */
+ * shape, library-owned memory, plain gradient steps (momentum 0.9, beta1 0.9, beta2 0.999, eps 1e-8 if another
+ * optimizer is chosen).  p, buffer_n, batch_n, lr, passes are left 0 for the caller to set. */
 void bmgd_default_config(bmgd_config* cfg);
 
 /* Algorithm 1's inputs (alpha, M via batch_n, T) plus the buffer capacity.  Defaults as above, theta = 0.
@@ -184,8 +200,12 @@ int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, 
  * softmax).  len must equal that count.  This is Algorithm 1's output when called after the last buffer. */
 int bmgd_get_theta(bmgd_ctx* ctx, float* host_out, int64_t len);
 
-/* Wait for all enqueued work, then overwrite theta (the initial value of Algorithm 1, or a checkpoint). */
+/* Wait for all enqueued work, then overwrite theta (the initial value of Algorithm 1, or a checkpoint).  The state
+ * of the optimizer is left as it is; bmgd_reset_optimizer() zeroes it. */
 int bmgd_set_theta(bmgd_ctx* ctx, const float* host_in, int64_t len);
+
+/* Wait for all enqueued work, then set the optimizer's state (v; m, s and the update count k) back to zero. */
+int bmgd_reset_optimizer(bmgd_ctx* ctx);
 
 /* Schedules (Theorem 4 lets the learning rate alpha_r and the number of passes T_r change with the iteration r;
  * Section 4 uses stage-wise T): both take effect for buffers run after the call, need no synchronisation and

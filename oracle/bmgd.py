@@ -34,6 +34,7 @@ from . import perm as _perm
 
 LINEAR, LOGISTIC, SOFTMAX = 0, 1, 2
 PER_PASS, FIXED = 0, 1
+SGD, MOMENTUM, NAG, ADAM = 0, 1, 2, 3
 
 
 def sigmoid(u: np.ndarray) -> np.ndarray:
@@ -111,6 +112,43 @@ class BMGD:
         self.lr_schedule = None if alphas is None or len(alphas) == 0 else np.asarray(alphas, dtype=np.float64)
         self.lr_pos = 0
 
+    def set_optimizer(self, kind: int, momentum: float = 0.9, beta1: float = 0.9, beta2: float = 0.999,
+                      eps: float = 1e-8) -> None:
+        """Buffered variants of other gradient methods (Section 4.3: the buffering idea combined with NAG and Adam):
+        the mini-batch gradient g of eq. (2.1) is fed to the chosen update rule instead of theta <- theta - alpha g.
+          MOMENTUM  v <- mu v - alpha g;  theta <- theta + v                       (heavy ball)
+          NAG       v <- mu v - alpha g;  theta <- theta + mu v - alpha g          (Nesterov, in the form that keeps
+                                                                                    the gradient at the stored iterate)
+          ADAM      m <- b1 m + (1 - b1) g;  s <- b2 s + (1 - b2) g^2;  k <- k + 1
+                    theta <- theta - alpha (m / (1 - b1^k)) / (sqrt(s / (1 - b2^k)) + eps)   (Kingma and Ba, Algorithm 1)
+        State starts at zero and is carried across buffers like theta."""
+        self.opt, self.mu, self.b1, self.b2, self.eps = kind, float(momentum), float(beta1), float(beta2), float(eps)
+        self.m = np.zeros_like(self.theta)
+        self.s = np.zeros_like(self.theta)
+        self.k = 0
+
+    def apply(self, g: np.ndarray) -> None:
+        """One update of theta from the mini-batch gradient g."""
+        a = self.step_size()
+        opt = getattr(self, "opt", SGD)
+        if opt == SGD:
+            self.theta = self.theta - a * g
+        elif opt == MOMENTUM:
+            self.m = self.mu * self.m - a * g
+            self.theta = self.theta + self.m
+        elif opt == NAG:
+            self.m = self.mu * self.m - a * g
+            self.theta = self.theta + self.mu * self.m - a * g
+        elif opt == ADAM:
+            self.k += 1
+            self.m = self.b1 * self.m + (1.0 - self.b1) * g
+            self.s = self.b2 * self.s + (1.0 - self.b2) * g * g
+            mhat = self.m / (1.0 - self.b1 ** self.k)
+            shat = self.s / (1.0 - self.b2 ** self.k)
+            self.theta = self.theta - a * mhat / (np.sqrt(shat) + self.eps)
+        else:
+            raise ValueError("unknown optimizer")
+
     def step_size(self) -> float:
         """Learning rate of the update about to be made."""
         if self.lr_schedule is None:
@@ -136,7 +174,7 @@ class BMGD:
                 idx = pm[start:min(start + self.n, N0)]
                 Xb = Xd[idx] if small else to_f64(X[idx])
                 g = minibatch_gradient(self.model, Xb, yd[idx], self.theta)
-                self.theta = self.theta - self.step_size() * g
+                self.apply(g)
                 self.steps += 1
                 self.lr_pos += 1
                 if on_step is not None:

@@ -22,11 +22,12 @@ BMGD_LINEAR, BMGD_LOGISTIC, BMGD_SOFTMAX = 0, 1, 2
 BMGD_F32, BMGD_BF16 = 0, 1
 BMGD_RESHUFFLE_PER_PASS, BMGD_RESHUFFLE_FIXED = 0, 1
 BMGD_CHAIN_AUTO, BMGD_CHAIN_PERSISTENT, BMGD_CHAIN_LAUNCH, BMGD_CHAIN_GRAM = 0, 1, 2, 3
+BMGD_OPT_SGD, BMGD_OPT_MOMENTUM, BMGD_OPT_NAG, BMGD_OPT_ADAM = 0, 1, 2, 3
 
 EXPORTS = [
     "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
     "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_device_buffer", "bmgd_get_theta",
-    "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_lr_schedule", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
+    "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_lr_schedule", "bmgd_reset_optimizer", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
     "bmgd_last_error", "bmgd_destroy",
 ]
 
@@ -37,7 +38,8 @@ class bmgd_config(C.Structure):
         ("passes", C.c_int32), ("model", C.c_int32), ("n_classes", C.c_int32), ("x_dtype", C.c_int32),
         ("seed", C.c_uint64), ("reshuffle", C.c_int32), ("n_buffers", C.c_int32), ("chain", C.c_int32),
         ("n_workgroups", C.c_int32), ("barrier_timeout_us", C.c_int64), ("workspace", C.c_void_p),
-        ("workspace_bytes", C.c_size_t),
+        ("workspace_bytes", C.c_size_t), ("optimizer", C.c_int32), ("reserved", C.c_int32),
+        ("momentum", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
     ]
 
 
@@ -72,6 +74,7 @@ def _load() -> C.CDLL:
     lib.bmgd_set_theta.argtypes, lib.bmgd_set_theta.restype = [vp, vp, i64], i32
     lib.bmgd_set_position.argtypes, lib.bmgd_set_position.restype = [vp, i64], i32
     lib.bmgd_set_lr.argtypes, lib.bmgd_set_lr.restype = [vp, C.c_double], i32
+    lib.bmgd_reset_optimizer.argtypes, lib.bmgd_reset_optimizer.restype = [vp], i32
     lib.bmgd_set_lr_schedule.argtypes, lib.bmgd_set_lr_schedule.restype = [vp, vp, C.c_int64], i32
     lib.bmgd_set_passes.argtypes, lib.bmgd_set_passes.restype = [vp, i32], i32
     lib.bmgd_get_perm.argtypes, lib.bmgd_get_perm.restype = [vp, i64, i32, vp, i64], i32
@@ -155,6 +158,10 @@ def bmgd_set_lr(ctx, lr) -> int:
     return lib.bmgd_set_lr(ctx, lr)
 
 
+def bmgd_reset_optimizer(ctx) -> int:
+    return lib.bmgd_reset_optimizer(ctx)
+
+
 def bmgd_set_lr_schedule(ctx, host_alphas, length) -> int:
     return lib.bmgd_set_lr_schedule(ctx, _ptr(host_alphas), length)
 
@@ -202,13 +209,15 @@ class Context:
 
     def __init__(self, p, buffer_n, batch_n, lr, passes, model=BMGD_LINEAR, n_classes=1, x_dtype=None,
                  seed=0, reshuffle=BMGD_RESHUFFLE_PER_PASS, n_buffers=0, chain=BMGD_CHAIN_AUTO,
-                 n_workgroups=0, barrier_timeout_us=0, workspace=None, workspace_bytes=0):
+                 n_workgroups=0, barrier_timeout_us=0, workspace=None, workspace_bytes=0, optimizer=BMGD_OPT_SGD,
+                 momentum=0.9, beta1=0.9, beta2=0.999, eps=1e-8):
         cfg = bmgd_default_config()
         cfg.p, cfg.buffer_n, cfg.batch_n, cfg.lr, cfg.passes = p, buffer_n, batch_n, lr, passes
         cfg.model, cfg.n_classes = model, n_classes
         cfg.x_dtype = (BMGD_BF16 if model == BMGD_SOFTMAX else BMGD_F32) if x_dtype is None else x_dtype
         cfg.seed, cfg.reshuffle, cfg.n_buffers = seed, reshuffle, n_buffers
         cfg.chain, cfg.n_workgroups, cfg.barrier_timeout_us = chain, n_workgroups, barrier_timeout_us
+        cfg.optimizer, cfg.momentum, cfg.beta1, cfg.beta2, cfg.eps = optimizer, momentum, beta1, beta2, eps
         if workspace is not None:
             cfg.workspace, cfg.workspace_bytes = _ptr(workspace), workspace_bytes
         self.cfg = cfg
@@ -245,6 +254,9 @@ class Context:
 
     def set_lr(self, lr):
         self._check(bmgd_set_lr(self.h, lr))
+
+    def reset_optimizer(self):
+        self._check(bmgd_reset_optimizer(self.h))
 
     def set_lr_schedule(self, alphas):
         a = np.ascontiguousarray([] if alphas is None else alphas, dtype=np.float32).reshape(-1)

@@ -24,20 +24,25 @@ def hipcc() -> str:
 def build(verbose: bool = True) -> str:
     """Always recompiles; returns the path of the shared library."""
     cc = hipcc()
-    objs = []
-    for src in SOURCES:
+    noise = "is not a recognized feature for this target"
+
+    def compile_one(src: str) -> str:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
         cmd = [cc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         res = subprocess.run(cmd, capture_output=True, text=True)
-        noise = "is not a recognized feature for this target"
         err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)
         if res.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{err}")
         if verbose and err.strip():
             print(err, file=sys.stderr)
-        objs.append(obj)
+        return obj
+
+    # the sources are independent: compile them side by side (a handful of processes)
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), 5)) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
     cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)

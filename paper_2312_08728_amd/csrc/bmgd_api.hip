@@ -25,7 +25,7 @@ constexpr int kMaxGroups = 256;                    // upper bound used to size t
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, total;
+    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, opt_m, opt_s, opt_len, total;
 };
 
 struct Slot {
@@ -83,6 +83,10 @@ struct bmgd_ctx {
     float* lr_tab_dev = nullptr;
     std::vector<float> lr_tab_host;
     int64_t lr_pos = 0;
+    // optimizer state (kind != BMGD_OPT_SGD): arrays laid out like theta, update count for Adam's bias corrections
+    float* opt_m = nullptr;
+    float* opt_s = nullptr;
+    int64_t opt_k = 0;
     uint32_t tag_epoch = 0;                        // tags handed out so far for flagged-word exchanges
     GlmLaunchShape shape{};
     int chain = BMGD_CHAIN_PERSISTENT;
@@ -131,6 +135,14 @@ bool valid_config(const bmgd_config& c, std::string* why)
         return bad("BMGD_CHAIN_GRAM needs the linear model and p <= 128");
     if (c.n_workgroups < 0 || c.n_workgroups > kMaxGroups) return bad("n_workgroups must be in [0, 256]");
     if (c.barrier_timeout_us < 0) return bad("barrier_timeout_us must be non-negative");
+    if (c.optimizer < BMGD_OPT_SGD || c.optimizer > BMGD_OPT_ADAM) return bad("unknown optimizer");
+    if (c.optimizer == BMGD_OPT_MOMENTUM || c.optimizer == BMGD_OPT_NAG) {
+        if (!(c.momentum >= 0.0 && c.momentum < 1.0)) return bad("momentum must be in [0, 1)");
+    }
+    if (c.optimizer == BMGD_OPT_ADAM) {
+        if (!(c.beta1 >= 0.0 && c.beta1 < 1.0) || !(c.beta2 >= 0.0 && c.beta2 < 1.0)) return bad("beta1 and beta2 must be in [0, 1)");
+        if (!(c.eps >= 0.0) || !std::isfinite(c.eps)) return bad("eps must be finite and non-negative");
+    }
     if (c.workspace != nullptr && (reinterpret_cast<uintptr_t>(c.workspace) % kAlign) != 0)
         return bad("workspace must be 256-byte aligned");
     if (c.model != BMGD_SOFTMAX) {
@@ -184,6 +196,18 @@ Layout make_layout(const bmgd_config& c)
         l.gram[0] = off; off += set;
         l.gram[1] = off; off += set;
         l.gram_perm = off; off += align_up((size_t)kMaxPassesPerLaunch * c.buffer_n * 4);   // second set of partitions
+    }
+    // optimizer state: like theta; with the redundant reduction every workgroup keeps a private copy (G * p <= 4096
+    // words there, rows padded to 16)
+    l.opt_m = l.opt_s = off;
+    l.opt_len = 0;
+    if (c.optimizer != BMGD_OPT_SGD) {
+        const size_t pp16 = ((size_t)c.p + 15) & ~size_t(15);
+        l.opt_len = c.model == BMGD_SOFTMAX ? (size_t)c.p * softmax_dims(c.p, c.batch_n, C).c_pad
+                                            : std::max<size_t>(pp16, 4096 + 16 * (size_t)kMaxGroups);
+        l.opt_m = off; off += align_up(l.opt_len * 4);
+        l.opt_s = off;
+        if (c.optimizer == BMGD_OPT_ADAM) off += align_up(l.opt_len * 4);
     }
     l.total = off;
     return l;
@@ -286,6 +310,20 @@ int drain(bmgd_ctx* ctx)
 
 int64_t batches_of(int64_t rows, int64_t n) { return (rows + n - 1) / n; }
 
+OptArgs opt_args(const bmgd_ctx* ctx, int64_t ahead)
+{
+    OptArgs o{};
+    o.kind = ctx->cfg.optimizer;
+    o.mu = (float)ctx->cfg.momentum;
+    o.b1 = (float)ctx->cfg.beta1;
+    o.b2 = (float)ctx->cfg.beta2;
+    o.eps = (float)ctx->cfg.eps;
+    o.m = ctx->opt_m;
+    o.s = ctx->opt_s;
+    o.k_base = (int)std::min<int64_t>(ctx->opt_k + ahead, 0x7FFFFFF0);
+    return o;
+}
+
 // Learning rate of the update `ahead` updates after those already enqueued.
 float rate_of(const bmgd_ctx* ctx, int64_t ahead)
 {
@@ -332,9 +370,10 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
             // the timing events are completed by the chain's dispatch; the stop event also frees set i
             HIP_TRY(ctx, gram_launch_chain(ctx->gram[i], ctx->theta, (int)rows, (int)c.p, (int)n, np, fixed ? 0 : (int)rows,
                                            (float)c.lr, lr_len ? ctx->lr_tab_dev : nullptr,
-                                           (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0)), lr_len, ctx->chain_stream, ev0,
-                                           ev1));
+                                           (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0)), lr_len, opt_args(ctx, 0),
+                                           ctx->chain_stream, ev0, ev1));
             ctx->lr_pos += (int64_t)np * M;
+            ctx->opt_k += (int64_t)np * M;
             ctx->chain_done[i] = ev1;                // stays valid until the records are settled, after a drain
             ctx->chain_pending[i] = true;
             ctx->open_chain.emplace_back(ev0, ev1);
@@ -363,6 +402,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
                     st.p = (int)c.p;
                     st.C = c.n_classes;
                     st.alpha = rate_of(ctx, (int64_t)i * M + m);
+                    st.opt = opt_args(ctx, (int64_t)i * M + m);
                     SoftmaxDims ds = d;
                     ds.c_pad = dmax.c_pad;           // W and WbT keep the strides fixed at creation
                     ds.p_pad = dmax.p_pad;
@@ -372,6 +412,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
             HIP_TRY(ctx, hipEventRecord(ev1, stream));
             ctx->open_chain.emplace_back(ev0, ev1);
             ctx->lr_pos += (int64_t)np * M;
+            ctx->opt_k += (int64_t)np * M;
             continue;
         }
         GlmArgs a{};
@@ -396,6 +437,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         a.lr_tab = lr_len ? ctx->lr_tab_dev : nullptr;
         a.lr_base = (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0));
         a.lr_len = lr_len;
+        a.opt = opt_args(ctx, 0);
         if ((int64_t)np * M >= (int64_t(1) << 23))
             return fail(ctx, BMGD_EINVAL, "passes per launch * batches per pass must stay below 2^23; use a larger batch_n");
         HIP_TRY(ctx, hipEventRecord(ev0, stream));
@@ -416,6 +458,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
                 a.single_step = (int)s;
                 a.alpha = rate_of(ctx, s);               // this mode passes the rate per launch
                 a.lr_tab = nullptr;
+                a.opt = opt_args(ctx, s);
                 const int64_t m = s % M;
                 const int nb = (int)std::min<int64_t>(n, rows - m * n);
                 HIP_TRY(ctx, glm_launch_step(ctx->shape, a, nb, stream));
@@ -424,6 +467,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         HIP_TRY(ctx, hipEventRecord(ev1, stream));
         ctx->open_chain.emplace_back(ev0, ev1);
         ctx->lr_pos += (int64_t)np * M;
+        ctx->opt_k += (int64_t)np * M;
     }
     ctx->steps += (int64_t)c.passes * M;
     ctx->sample_gradients += (int64_t)c.passes * rows;
@@ -468,6 +512,11 @@ BMGD_API void bmgd_default_config(bmgd_config* cfg)
     cfg->x_dtype = BMGD_F32;
     cfg->reshuffle = BMGD_RESHUFFLE_PER_PASS;
     cfg->chain = BMGD_CHAIN_AUTO;
+    cfg->optimizer = BMGD_OPT_SGD;
+    cfg->momentum = 0.9;
+    cfg->beta1 = 0.9;
+    cfg->beta2 = 0.999;
+    cfg->eps = 1e-8;
 }
 
 BMGD_API size_t bmgd_workspace_bytes(const bmgd_config* cfg)
@@ -544,6 +593,9 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->gram[1] = reinterpret_cast<float*>(base + ctx->lay.gram[1]);
     ctx->gram_perm[0] = ctx->perm;
     ctx->gram_perm[1] = reinterpret_cast<int32_t*>(base + ctx->lay.gram_perm);
+    ctx->opt_m = reinterpret_cast<float*>(base + ctx->lay.opt_m);
+    ctx->opt_s = reinterpret_cast<float*>(base + ctx->lay.opt_s);
+    if (ctx->lay.total > ctx->lay.opt_m) CREATE_TRY(hipMemset(ctx->opt_m, 0, ctx->lay.total - ctx->lay.opt_m));
     CREATE_TRY(hipMemset(ctx->sync, 0, 64));
     if (cfg->model == BMGD_SOFTMAX) {
         // theta = 0 (padding classes included), bf16 copy = 0, residual scratch = 0
@@ -568,6 +620,7 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
             ctx->err = msg;
             return bail(BMGD_EINVAL);
         }
+        ctx->shape.with_optimizer = cfg->optimizer != BMGD_OPT_SGD;
         CREATE_TRY(glm_prepare(&ctx->shape));
         ctx->chain = resolve_chain(ctx->cfg);
         if (ctx->chain == BMGD_CHAIN_GRAM) {
@@ -722,6 +775,16 @@ BMGD_API int bmgd_set_lr(bmgd_ctx* ctx, double lr)
     if (!ctx) return BMGD_EINVAL;
     if (!(lr > 0.0) || !std::isfinite(lr)) return fail(ctx, BMGD_EINVAL, "lr must be finite and positive");
     ctx->cfg.lr = lr;
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_reset_optimizer(bmgd_ctx* ctx)
+{
+    if (!ctx) return BMGD_EINVAL;
+    const int rc = drain(ctx);
+    if (rc != BMGD_OK) return rc;
+    if (ctx->lay.total > ctx->lay.opt_m) HIP_TRY(ctx, hipMemset(ctx->opt_m, 0, ctx->lay.total - ctx->lay.opt_m));
+    ctx->opt_k = 0;
     return BMGD_OK;
 }
 

@@ -28,6 +28,41 @@ hipError_t launch_perm(int32_t* out, int64_t rows, int npass, const PermKeys& ke
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------------
+// Update rules fed with the mini-batch gradient (Section 4.3: buffered NAG and Adam).
+
+enum { kOptSgd = 0, kOptMomentum = 1, kOptNag = 2, kOptAdam = 3 };
+
+struct OptArgs {
+    int kind;
+    float mu, b1, b2, eps;
+    float* m;           // first state array (v of momentum / NAG, m of Adam), laid out like theta
+    float* s;           // second state array (Adam)
+    int k_base;         // updates made before this launch (Adam's bias corrections use k_base + step + 1)
+};
+
+#ifdef __HIPCC__
+// Bias corrections 1 / (1 - beta^k) of Adam for update number k >= 1.
+__device__ __forceinline__ void opt_corrections(const OptArgs& o, int k, float& c1, float& c2)
+{
+    c1 = 1.f / (1.f - powf(o.b1, (float)k));
+    c2 = 1.f / (1.f - powf(o.b2, (float)k));
+}
+
+// One coordinate of one update: new theta from the mean gradient g; m and s are that coordinate's state.
+__device__ __forceinline__ float opt_update(const OptArgs& o, float th, float g, float alpha, float& m, float& s, float c1,
+                                            float c2)
+{
+    if (o.kind == kOptAdam) {
+        m = o.b1 * m + (1.f - o.b1) * g;
+        s = o.b2 * s + (1.f - o.b2) * g * g;
+        return th - alpha * (m * c1) / (sqrtf(s * c2) + o.eps);
+    }
+    m = o.mu * m - alpha * g;
+    return o.kind == kOptNag ? th + o.mu * m - alpha * g : th + m;
+}
+#endif
+
+// ---------------------------------------------------------------------------------------------------
 // GLM (least squares / logistic) chain.
 
 enum { kReduceRedundant = 0, kReduceSliced = 1 };
@@ -43,6 +78,7 @@ struct GlmLaunchShape {
     int reduce_mode;    // kReduce*
     size_t lds_bytes;
     int max_G;          // co-resident workgroups the device can hold for this kernel
+    int with_optimizer; // set by the caller after glm_plan: the kernel variant with an update rule other than the plain step
 };
 
 struct GlmArgs {
@@ -64,6 +100,8 @@ struct GlmArgs {
     float alpha;
     long long timeout_ticks;
     int single_step;        // >= 0: process only that step and stop after writing partial sums
+    OptArgs opt;            // kind == kOptSgd: plain steps, no state.  Redundant reduction: every workgroup keeps a
+                            // private copy of the state at m + blockIdx.x * pp (all copies stay identical)
     const float* lr_tab;    // optional learning rate per step: step s uses lr_tab[min(lr_base + s, lr_len - 1)]
     int lr_base, lr_len;
 };
@@ -94,8 +132,8 @@ hipError_t gram_launch_moments(const float* X, const float* y, const int32_t* pe
 // The npass * ceil(rows / n) updates of theta from those matrices, in one workgroup.
 // lr_tab (may be NULL): learning rate of step s is lr_tab[min(lr_base + s, lr_len - 1)] instead of alpha.
 hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, int n, int npass, int perm_stride, float alpha,
-                             const float* lr_tab, int lr_base, int lr_len, hipStream_t stream, hipEvent_t start,
-                             hipEvent_t stop);
+                             const float* lr_tab, int lr_base, int lr_len, const OptArgs& opt, hipStream_t stream,
+                             hipEvent_t start, hipEvent_t stop);
 
 // ---------------------------------------------------------------------------------------------------
 // Softmax regression (bf16 predictors, fp32 master weights) on the matrix cores.
@@ -115,6 +153,7 @@ struct SoftmaxStep {
     const int32_t* idx;     // the mini-batch: nb entries of the partition
     const void* XT;         // bf16 [p][n_pad]: this mini-batch transposed
     float* W;               // fp32 master [p][c_pad]
+    OptArgs opt;            // state arrays laid out like W; k_base = updates made before this one
     void* WbT;              // bf16 copy, transposed [c_pad][p_pad]
     float* U;               // logits scratch [splits][m_pad][c_pad]
     void* Rt;               // residual scratch, bf16 [c_pad][n_pad]

@@ -238,14 +238,15 @@ __device__ __forceinline__ void gather_columns_impl(const ExchangeCtx& x, const 
 // new values in kThetaCopies copies (a workgroup polls copy (its index mod kThetaCopies), so no single set
 // of words is polled by the whole grid); then everyone collects the whole updated theta into th_lds.
 // Returns true when a wait ran out.
+template <class F>
 __device__ __forceinline__ bool sliced_update(const ExchangeCtx& x, const unsigned long long* words,
-                                              unsigned long long* thw, float* th_lds, float scale, unsigned tag)
+                                              unsigned long long* thw, float* th_lds, unsigned tag, F&& new_theta)
 {
     const int cw = ((x.p + x.G - 1) / x.G + 15) & ~15;   // slices are whole lines of 16 words
     const int c_lo = min(x.p, (int)blockIdx.x * cw), c_hi = min(x.p, c_lo + cw);
     const int pp = x.pp;
     gather_columns_impl(x, words, c_lo, c_hi, tag, [&](int c, float t) {
-        const float v = th_lds[c] - scale * t;
+        const float v = new_theta(c, t);
 #pragma unroll
         for (int r = 0; r < kThetaCopies; ++r) ll_store(thw + (size_t)r * pp + c, v, tag);
     });
@@ -293,7 +294,9 @@ struct RowGroup {
 //               of the same wavefront) nor the compute ever waits for HBM latency.
 enum { kPipeWide = 0, kPipeGroups = 1, kPipeAhead = 2 };
 
-template <int V, int CPL, int PF, bool THL, int PIPE, int BLOCK>
+// OPT: an update rule other than the plain step (its state lives in global memory, see GlmArgs::opt); a separate
+// instantiation so that the plain path carries none of it.
+template <int V, int CPL, int PF, bool THL, int PIPE, int BLOCK, bool OPT>
 __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
 {
     extern __shared__ __align__(16) float smem[];
@@ -479,6 +482,19 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
         __syncthreads();
 
         const float scale = alpha_s / (float)nb;
+        // new value of theta[c] from the batch sum t of column c; `si` is where that coordinate's optimizer state lives
+        float oc1 = 1.f, oc2 = 1.f;
+        if constexpr (OPT) {
+            if (a.opt.kind == kOptAdam) opt_corrections(a.opt, a.opt.k_base + (s - first) + 1, oc1, oc2);
+        }
+        auto apply_update = [&](int c, int si, float t) -> float {
+            if constexpr (!OPT) return th_lds[c] - scale * t;
+            float m = a.opt.m[si], sv = a.opt.kind == kOptAdam ? a.opt.s[si] : 0.f;
+            const float v = opt_update(a.opt, th_lds[c], t / (float)nb, alpha_s, m, sv, oc1, oc2);
+            a.opt.m[si] = m;
+            if (a.opt.kind == kOptAdam) a.opt.s[si] = sv;
+            return v;
+        };
         if (a.single_step >= 0) {
             // step-per-launch: plain partial sums, a second kernel reduces and updates
             float* part = a.partial + (size_t)(s & 1) * G * p;
@@ -494,7 +510,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
             for (int c = tid; c < p; c += BLOCK) {
                 float t = 0.f;
                 for (int w = 0; w < NW; ++w) t += wpart[w * p + c];
-                th_lds[c] -= scale * t;
+                th_lds[c] = apply_update(c, c, t);
             }
             __syncthreads();
             if constexpr (AHEAD) advance_rows(s);
@@ -518,10 +534,13 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
             if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
         }
         if (a.reduce_mode == kReduceRedundant) {
-            gather_columns(words, 0, p, tag, [&](int c, float t) { th_lds[c] -= scale * t; });
+            // every workgroup applies the same update to its own copy of theta and of the optimizer's state
+            gather_columns(words, 0, p, tag, [&](int c, float t) { th_lds[c] = apply_update(c, (int)blockIdx.x * pp + c, t); });
             if (s_abort) return;
         } else {
-            if (sliced_update(xc, words, a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp, th_lds, scale, tag)) return;
+            if (sliced_update(xc, words, a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp, th_lds, tag,
+                              [&](int c, float t) { return apply_update(c, c, t); }))
+                return;
         }
         if constexpr (AHEAD) advance_rows(s);
         load_theta_regs();
@@ -532,15 +551,25 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
     }
 }
 
-// Step-per-launch companion: theta[c] -= scale * sum_g partial[g][c], one thread per column.
+// Step-per-launch companion: one thread per column sums the workgroups' partial sums and applies the update
+// (opt.k_base = updates made before this one).
 __global__ void __launch_bounds__(256) glm_update_kernel(float* __restrict__ theta, const float* __restrict__ part,
-                                                         int p, int G, float scale)
+                                                         int p, int G, float alpha, float inv_nb, OptArgs opt)
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= p) return;
     float t = 0.f;
     for (int g = 0; g < G; ++g) t += part[(size_t)g * p + c];
-    theta[c] -= scale * t;
+    if (opt.kind == kOptSgd) {
+        theta[c] -= alpha * inv_nb * t;
+        return;
+    }
+    float c1 = 1.f, c2 = 1.f;
+    if (opt.kind == kOptAdam) opt_corrections(opt, opt.k_base + 1, c1, c2);
+    float m = opt.m[c], sv = opt.kind == kOptAdam ? opt.s[c] : 0.f;
+    theta[c] = opt_update(opt, theta[c], t * inv_nb, alpha, m, sv, c1, c2);
+    opt.m[c] = m;
+    if (opt.kind == kOptAdam) opt.s[c] = sv;
 }
 
 using KernelFn = void (*)(GlmArgs);
@@ -562,60 +591,66 @@ int max_pf(int v, int cpl)
     return pf;
 }
 
-template <int V, int CPL, int PF, int PIPE>
+template <bool OPT, int V, int CPL, int PF, int PIPE>
 KernelFn pick()
 {
     if constexpr (!shape_ok(V, CPL, PF, PIPE)) {
         return nullptr;
     } else {
         constexpr bool wide = CPL >= 8;
-        return glm_chain_kernel<V, CPL, PF, wide, PIPE, wide ? 512 : 1024>;
+        return glm_chain_kernel<V, CPL, PF, wide, PIPE, wide ? 512 : 1024, OPT>;
     }
 }
 
-template <int V, int CPL, int PF>
+template <bool OPT, int V, int CPL, int PF>
 KernelFn pick_pipe(int pipe)
 {
     switch (pipe) {
-    case kPipeWide: return pick<V, CPL, PF, kPipeWide>();
-    case kPipeGroups: return pick<V, CPL, PF, kPipeGroups>();
-    case kPipeAhead: return pick<V, CPL, PF, kPipeAhead>();
+    case kPipeWide: return pick<OPT, V, CPL, PF, kPipeWide>();
+    case kPipeGroups: return pick<OPT, V, CPL, PF, kPipeGroups>();
+    case kPipeAhead: return pick<OPT, V, CPL, PF, kPipeAhead>();
     }
     return nullptr;
 }
 
-template <int V, int CPL>
+template <bool OPT, int V, int CPL>
 KernelFn pick_pf(int pf, int pipe)
 {
     switch (pf) {
-    case 1: return pick_pipe<V, CPL, 1>(pipe);
-    case 2: return pick_pipe<V, CPL, 2>(pipe);
-    case 4: return pick_pipe<V, CPL, 4>(pipe);
+    case 1: return pick_pipe<OPT, V, CPL, 1>(pipe);
+    case 2: return pick_pipe<OPT, V, CPL, 2>(pipe);
+    case 4: return pick_pipe<OPT, V, CPL, 4>(pipe);
     }
     return nullptr;
 }
 
-template <int V>
+template <bool OPT, int V>
 KernelFn pick_v(int cpl, int pf, int pipe)
 {
     switch (cpl) {
-    case 1: return pick_pf<V, 1>(pf, pipe);
-    case 2: return pick_pf<V, 2>(pf, pipe);
-    case 4: return pick_pf<V, 4>(pf, pipe);
-    case 8: return pick_pf<V, 8>(pf, pipe);
-    case 16: return pick_pf<V, 16>(pf, pipe);
+    case 1: return pick_pf<OPT, V, 1>(pf, pipe);
+    case 2: return pick_pf<OPT, V, 2>(pf, pipe);
+    case 4: return pick_pf<OPT, V, 4>(pf, pipe);
+    case 8: return pick_pf<OPT, V, 8>(pf, pipe);
+    case 16: return pick_pf<OPT, V, 16>(pf, pipe);
+    }
+    return nullptr;
+}
+
+template <bool OPT>
+KernelFn pick_kernel_opt(const GlmLaunchShape& s)
+{
+    switch (s.V) {
+    case 1: return pick_v<OPT, 1>(s.CPL, s.PF, s.pipe);
+    case 2: return pick_v<OPT, 2>(s.CPL, s.PF, s.pipe);
+    case 4: return pick_v<OPT, 4>(s.CPL, s.PF, s.pipe);
     }
     return nullptr;
 }
 
 KernelFn pick_kernel(const GlmLaunchShape& s)
 {
-    switch (s.V) {
-    case 1: return pick_v<1>(s.CPL, s.PF, s.pipe);
-    case 2: return pick_v<2>(s.CPL, s.PF, s.pipe);
-    case 4: return pick_v<4>(s.CPL, s.PF, s.pipe);
-    }
-    return nullptr;
+    return s.with_optimizer ? pick_kernel_opt<true>(s) : pick_kernel_opt<false>(s);
 }
 
 
@@ -717,7 +752,7 @@ hipError_t glm_launch_step(const GlmLaunchShape& s, const GlmArgs& args, int nb,
     if (e != hipSuccess) return e;
     const float* part = args.partial + (size_t)(args.single_step & 1) * s.G * args.p;
     hipLaunchKernelGGL(glm_update_kernel, dim3((args.p + 255) / 256), dim3(256), 0, stream, args.theta, part,
-                       args.p, s.G, args.alpha / (float)nb);
+                       args.p, s.G, args.alpha, 1.f / (float)nb, args.opt);
     return hipGetLastError();
 }
 

@@ -176,10 +176,11 @@ __global__ void __launch_bounds__(64 * kGramWaves) gram_mfma_kernel(const float*
 
 // The chain: one workgroup, theta in LDS (two copies, alternating), the matrices of the coming AHEAD steps
 // already in registers.  Thread (i, seg) = (t / TPR, t % TPR); the TPR lanes of a row add up their parts.
-template <int TPR, int KQ, int KS, int AHEAD, bool TAB>
+// OPT: an update rule other than the plain step: separate instantiations, the plain path carries none of it.
+template <int TPR, int KQ, int KS, int AHEAD, bool TAB, bool OPT>
 __global__ void __launch_bounds__(1024) gram_chain_kernel(const float* __restrict__ gram, float* __restrict__ theta,
                                                           GramLayout L, int nsteps, int period, float alpha,
-                                                          const float* __restrict__ lr_tab, int lr_base, int lr_len)
+                                                          const float* __restrict__ lr_tab, int lr_base, int lr_len, OptArgs opt)
 {
     __shared__ __align__(16) float th[2][kGramMaxP + 4 * 16];
     const int t = threadIdx.x;
@@ -222,6 +223,13 @@ __global__ void __launch_bounds__(1024) gram_chain_kernel(const float* __restric
 
     // Steps are taken AHEAD at a time without any branch around the loads (a branch would make the compiler
     // wait for every outstanding load); steps past the last one run with a zero learning rate.
+    // optimizer state of coordinate i lives in the registers of the lane that updates it
+    const bool owner = seg == 0 && row_ok;
+    float om = 0.f, os = 0.f;
+    if (OPT && owner) {
+        om = opt.m[i];
+        if (opt.kind == kOptAdam) os = opt.s[i];
+    }
     int cur = 0;
     for (int sb = 0; sb < nsteps; sb += AHEAD) {
 #pragma unroll
@@ -251,12 +259,26 @@ __global__ void __launch_bounds__(1024) gram_chain_kernel(const float* __restric
             if (TPR >= 4) dot += dpp_mov<0x4E>(dot);      // lanes ^2
             if (TPR >= 8) dot += dpp_mov<0x141>(dot);     // mirror within 8
             if (TPR >= 16) dot += dpp_mov<0x140>(dot);    // mirror within 16
-            if (seg == 0 && row_ok) th[cur ^ 1][i] = fmaf(-a_eff, dot, base);
+            if constexpr (!OPT) {
+                if (owner) th[cur ^ 1][i] = fmaf(-a_eff, dot, base);
+            } else if (owner) {
+                float nv = th[cur][i];
+                if (sb + d < nsteps) {               // steps past the last one leave theta and the state alone
+                    float c1 = 1.f, c2 = 1.f;
+                    if (opt.kind == kOptAdam) opt_corrections(opt, opt.k_base + sb + d + 1, c1, c2);
+                    nv = opt_update(opt, nv, dot - bb[d], a_eff, om, os, c1, c2);
+                }
+                th[cur ^ 1][i] = nv;
+            }
             __syncthreads();
             cur ^= 1;
         }
     }
     for (int c = t; c < p; c += blockDim.x) theta[c] = th[cur][c];
+    if (OPT && owner) {
+        opt.m[i] = om;
+        if (opt.kind == kOptAdam) opt.s[i] = os;
+    }
 }
 
 GramLayout make_layout(int p)
@@ -307,29 +329,33 @@ hipError_t launch_gram_mfma(bool wide, dim3 grid, size_t lds, hipStream_t stream
 
 template <int TPR, int KQ, int KS>
 hipError_t launch_chain(const GramLayout& L, const float* gram, float* theta, int nsteps, int period, float alpha, const float* lr_tab,
-                        int lr_base, int lr_len, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
+                        int lr_base, int lr_len, const OptArgs& opt, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
 {
     constexpr int per_step = 4 * KQ + KS + 1;
     constexpr int AHEAD = per_step <= 9 ? 8 : per_step <= 14 ? 6 : 4;
-    if (lr_tab)
-        hipExtLaunchKernelGGL((gram_chain_kernel<TPR, KQ, KS, AHEAD, true>), dim3(1), dim3(L.nthr), 0u, stream, start, stop, 0u, gram,
-                              theta, L, nsteps, period, alpha, lr_tab, lr_base, lr_len);
-    else
-        hipExtLaunchKernelGGL((gram_chain_kernel<TPR, KQ, KS, AHEAD, false>), dim3(1), dim3(L.nthr), 0u, stream, start, stop, 0u, gram,
-                              theta, L, nsteps, period, alpha, lr_tab, lr_base, lr_len);
+    auto go = [&](auto kernel) {
+        hipExtLaunchKernelGGL(kernel, dim3(1), dim3(L.nthr), 0u, stream, start, stop, 0u, gram, theta, L, nsteps, period, alpha, lr_tab,
+                              lr_base, lr_len, opt);
+    };
+    const bool with_opt = opt.kind != kOptSgd;
+    if (lr_tab && with_opt) go(gram_chain_kernel<TPR, KQ, KS, AHEAD, true, true>);
+    else if (lr_tab) go(gram_chain_kernel<TPR, KQ, KS, AHEAD, true, false>);
+    else if (with_opt) go(gram_chain_kernel<TPR, KQ, KS, AHEAD, false, true>);
+    else go(gram_chain_kernel<TPR, KQ, KS, AHEAD, false, false>);
     return hipGetLastError();
 }
 
 template <int TPR, int KQ>
 hipError_t launch_chain_ks(const GramLayout& L, const float* gram, float* theta, int nsteps, int period, float alpha,
-                           const float* lr_tab, int lr_base, int lr_len, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
+                           const float* lr_tab, int lr_base, int lr_len, const OptArgs& opt, hipStream_t stream, hipEvent_t start,
+                           hipEvent_t stop)
 {
     switch (L.ks) {
-    case 0: return launch_chain<TPR, KQ, 0>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
-    case 1: return launch_chain<TPR, KQ, 1>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
-    case 2: return launch_chain<TPR, KQ, 2>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
-    case 3: return launch_chain<TPR, KQ, 3>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
-    case 4: return launch_chain<TPR, KQ, 4>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+    case 0: return launch_chain<TPR, KQ, 0>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
+    case 1: return launch_chain<TPR, KQ, 1>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
+    case 2: return launch_chain<TPR, KQ, 2>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
+    case 3: return launch_chain<TPR, KQ, 3>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
+    case 4: return launch_chain<TPR, KQ, 4>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
     }
     return hipErrorInvalidValue;
 }
@@ -386,7 +412,8 @@ hipError_t gram_launch_moments(const float* X, const float* y, const int32_t* pe
 }
 
 hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, int n, int npass, int perm_stride, float alpha,
-                             const float* lr_tab, int lr_base, int lr_len, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
+                             const float* lr_tab, int lr_base, int lr_len, const OptArgs& opt, hipStream_t stream,
+                             hipEvent_t start, hipEvent_t stop)
 {
     if (p < 1 || p > kGramMaxP) return hipErrorInvalidValue;
     const GramLayout L = make_layout(p);
@@ -394,14 +421,14 @@ hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, i
     const int nsteps = M * npass, period = perm_stride == 0 ? M : nsteps;
     if (L.tpr == 16) {
         switch (L.kq) {
-        case 0: return launch_chain_ks<16, 0>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
-        case 1: return launch_chain_ks<16, 1>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+        case 0: return launch_chain_ks<16, 0>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
+        case 1: return launch_chain_ks<16, 1>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
         }
     } else {
         switch (L.kq) {
-        case 2: return launch_chain_ks<8, 2>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
-        case 3: return launch_chain_ks<8, 3>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
-        case 4: return launch_chain_ks<8, 4>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, stream, start, stop);
+        case 2: return launch_chain_ks<8, 2>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
+        case 3: return launch_chain_ks<8, 3>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
+        case 4: return launch_chain_ks<8, 4>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
         }
     }
     return hipErrorInvalidValue;

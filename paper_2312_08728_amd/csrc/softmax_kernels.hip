@@ -90,7 +90,9 @@ struct GemmArgs {
     float* W;                   // [p][ldw] fp32 master
     unsigned short* WbT;        // [ldw][ldwt] bf16 copy, transposed
     int ldw, ldwt;
-    float scale;
+    float scale;                // alpha / n_b
+    float alpha, inv_nb;
+    OptArgs opt;                // state arrays [p][ldw] like W; plain steps if kind == kOptSgd
     int tiles_m, tiles_n, splits;   // work items = splits * tiles_m * tiles_n, dealt to XCDs in contiguous runs
 };
 
@@ -99,7 +101,8 @@ struct GemmArgs {
 // ~1 us, so the loop would otherwise run at memory latency.
 constexpr int kDepth = 4;
 
-template <bool UPDATE>
+// OPT (with UPDATE): an update rule other than the plain step, in an instantiation of its own.
+template <bool UPDATE, bool OPT = false>
 __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
 {
     __shared__ __align__(16) unsigned short As[2][TM * LDS_STRIDE];
@@ -219,6 +222,8 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
                     if (r < g.m_pad && c < g.ldu) U[(size_t)r * g.ldu + c] = acc[i][j][v];
                 }
     } else {
+        float oc1 = 1.f, oc2 = 1.f;
+        if (OPT && g.opt.kind == kOptAdam) opt_corrections(g.opt, g.opt.k_base + 1, oc1, oc2);
         // rows are features, columns are classes: W[r][c] -= scale * acc; bf16 copy goes out transposed.
         // The 32 master weights of a half-quadrant are requested together, from clamped addresses and without a
         // branch, and only then combined and stored (a branch around each load would wait for it on the spot).
@@ -241,7 +246,17 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
                     const int lc = wn + j * 32 + ccol;
                     const int r = m0 + lr, c = n0 + lc;
                     const bool ok = r < g.M && c < g.ldw;
-                    const float w = ok ? wv[j][v] - g.scale * acc[i][j][v] : 0.f;
+                    float w = 0.f;
+                    if constexpr (!OPT) {
+                        w = ok ? wv[j][v] - g.scale * acc[i][j][v] : 0.f;
+                    } else if (ok) {
+                        // the state is read here, element by element: this path trades speed for the extra arrays
+                        const size_t at = (size_t)r * g.ldw + c;
+                        float m = g.opt.m[at], sv = g.opt.kind == kOptAdam ? g.opt.s[at] : 0.f;
+                        w = opt_update(g.opt, wv[j][v], acc[i][j][v] * g.inv_nb, g.alpha, m, sv, oc1, oc2);
+                        g.opt.m[at] = m;
+                        if (g.opt.kind == kOptAdam) g.opt.s[at] = sv;
+                    }
                     if (ok) g.W[(size_t)r * g.ldw + c] = w;
                     Ts[lc * (TM + 8) + lr] = f32_to_bf16_rne(w);
                 }
@@ -467,10 +482,16 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
     h.ldw = d.c_pad;
     h.ldwt = d.p_pad;
     h.scale = s.alpha / (float)s.nb;
+    h.alpha = s.alpha;
+    h.inv_nb = 1.f / (float)s.nb;
+    h.opt = s.opt;
     h.tiles_m = d.p_pad / TM;
     h.tiles_n = d.c_pad / TN;
     h.splits = 1;
-    hipLaunchKernelGGL(gemm_nt_kernel<true>, dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(256), 0, stream, h);
+    if (s.opt.kind != kOptSgd)
+        hipLaunchKernelGGL((gemm_nt_kernel<true, true>), dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(256), 0, stream, h);
+    else
+        hipLaunchKernelGGL((gemm_nt_kernel<true, false>), dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(256), 0, stream, h);
     return hipGetLastError();
 }
 
