@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
 # HBM traffic of one launch of the chain kernel on the primary workload, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE (see profiles/); only valid for the kernel source it was measured on.
-TRAFFIC = {"cfg2": {"kernel_sha256": "7a6b1cb121ecbc902ca03bd6adc7ef2c7dc74f501d0fe4bdabe89a3121524496", "bytes_per_launch": 177382988}}
+TRAFFIC = {"cfg2": {"kernel_sha256": "aa0950e8785d378071d84f7b28c078e8102dd81c98d570148c2c12b4690f229e", "bytes_per_launch": 178923765}}
 
 
 def _kernel_sha() -> str:
