@@ -32,7 +32,8 @@ struct Slot {
     void* x = nullptr;
     void* y = nullptr;
     int64_t rows = 0;
-    hipEvent_t copy_done = nullptr;                // recorded on the copy stream after the slot is filled
+    hipEvent_t copy_done = nullptr;                // the copy_end event of the slot's last load (owned by its RunRecord):
+                                                   // one marker on the copy stream serves timing and ordering
     hipEvent_t compute_done = nullptr;             // recorded on the compute stream after the slot was read
     bool was_read = false;
 };
@@ -488,7 +489,6 @@ void destroy_ctx(bmgd_ctx* ctx)
     give_event(ctx, ctx->pending_copy.copy_end);
     for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
     for (Slot& s : ctx->slots) {
-        if (s.copy_done) (void)hipEventDestroy(s.copy_done);
         if (s.compute_done) (void)hipEventDestroy(s.compute_done);
     }
     if (ctx->base) (void)hipEventDestroy(ctx->base);
@@ -576,7 +576,6 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     for (int s = 0; s < 2; ++s) {
         ctx->slots[s].x = base + ctx->lay.slot_x[s];
         ctx->slots[s].y = base + ctx->lay.slot_y[s];
-        CREATE_TRY(hipEventCreate(&ctx->slots[s].copy_done));
         CREATE_TRY(hipEventCreate(&ctx->slots[s].compute_done));
     }
     ctx->perm = reinterpret_cast<int32_t*>(base + ctx->lay.perm);
@@ -663,7 +662,7 @@ BMGD_API int bmgd_load_buffer_async(bmgd_ctx* ctx, const void* host_x, const voi
     HIP_TRY(ctx, hipMemcpyAsync(slot.x, host_x, xbytes, hipMemcpyHostToDevice, cs));
     HIP_TRY(ctx, hipMemcpyAsync(slot.y, host_y, ybytes, hipMemcpyHostToDevice, cs));
     HIP_TRY(ctx, hipEventRecord(rec.copy_end, cs));
-    HIP_TRY(ctx, hipEventRecord(slot.copy_done, cs));
+    slot.copy_done = rec.copy_end;
     rec.has_copy = true;
     slot.rows = rows;
     ctx->h2d_bytes += (int64_t)(xbytes + ybytes);
