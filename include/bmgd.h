@@ -228,6 +228,13 @@ int bmgd_set_position(bmgd_ctx* ctx, int64_t buffer_counter);
  * pass, len) exactly as a run would use it (pass 0 = the fixed-mode partition).  Blocks. */
 int bmgd_get_perm(bmgd_ctx* ctx, int64_t buffer_counter, int pass, int32_t* host_out, int64_t len);
 
+/* Evaluation (the experiments of Section 4 report the loss / mean squared error along the run): wait for all
+ * enqueued work, then compute on `stream` the mean over the rows of a device-resident buffer of the per-sample
+ * loss at the current theta -- (x'theta - y)^2 / 2, log(1 + e^u) - y u with u = x'theta, or the softmax
+ * cross-entropy (logits from the bf16 copy of W, as in the updates) -- and return it in *host_out.  fp32 per row,
+ * fp64 sums in a fixed order.  dev_x, dev_y, rows as for bmgd_run_device_buffer (rows may exceed buffer_n).  Blocks. */
+int bmgd_eval_loss(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* stream, double* host_out);
+
 /* Wait for all enqueued work (both streams last used) and report a device-side time-out if one happened. */
 int bmgd_sync(bmgd_ctx* ctx);
 

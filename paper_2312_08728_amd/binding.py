@@ -27,7 +27,7 @@ BMGD_OPT_SGD, BMGD_OPT_MOMENTUM, BMGD_OPT_NAG, BMGD_OPT_ADAM = 0, 1, 2, 3
 EXPORTS = [
     "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
     "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_device_buffer", "bmgd_get_theta",
-    "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_lr_schedule", "bmgd_reset_optimizer", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
+    "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_lr_schedule", "bmgd_reset_optimizer", "bmgd_eval_loss", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
     "bmgd_last_error", "bmgd_destroy",
 ]
 
@@ -74,6 +74,7 @@ def _load() -> C.CDLL:
     lib.bmgd_set_theta.argtypes, lib.bmgd_set_theta.restype = [vp, vp, i64], i32
     lib.bmgd_set_position.argtypes, lib.bmgd_set_position.restype = [vp, i64], i32
     lib.bmgd_set_lr.argtypes, lib.bmgd_set_lr.restype = [vp, C.c_double], i32
+    lib.bmgd_eval_loss.argtypes, lib.bmgd_eval_loss.restype = [vp, vp, vp, C.c_int64, vp, C.POINTER(C.c_double)], i32
     lib.bmgd_reset_optimizer.argtypes, lib.bmgd_reset_optimizer.restype = [vp], i32
     lib.bmgd_set_lr_schedule.argtypes, lib.bmgd_set_lr_schedule.restype = [vp, vp, C.c_int64], i32
     lib.bmgd_set_passes.argtypes, lib.bmgd_set_passes.restype = [vp, i32], i32
@@ -156,6 +157,12 @@ def bmgd_set_theta(ctx, host_in, length) -> int:
 
 def bmgd_set_lr(ctx, lr) -> int:
     return lib.bmgd_set_lr(ctx, lr)
+
+
+def bmgd_eval_loss(ctx, dev_x, dev_y, rows, stream=None):
+    out = C.c_double(0.0)
+    rc = lib.bmgd_eval_loss(ctx, _ptr(dev_x), _ptr(dev_y), rows, _stream(stream), C.byref(out))
+    return rc, out.value
 
 
 def bmgd_reset_optimizer(ctx) -> int:
@@ -254,6 +261,11 @@ class Context:
 
     def set_lr(self, lr):
         self._check(bmgd_set_lr(self.h, lr))
+
+    def eval_loss(self, dev_x, dev_y, rows, stream=None) -> float:
+        rc, v = bmgd_eval_loss(self.h, dev_x, dev_y, rows, stream)
+        self._check(rc)
+        return v
 
     def reset_optimizer(self):
         self._check(bmgd_reset_optimizer(self.h))

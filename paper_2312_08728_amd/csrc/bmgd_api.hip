@@ -25,7 +25,7 @@ constexpr int kMaxGroups = 256;                    // upper bound used to size t
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, opt_m, opt_s, opt_len, total;
+    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, opt_m, opt_s, opt_len, eval, total;
 };
 
 struct Slot {
@@ -210,6 +210,7 @@ Layout make_layout(const bmgd_config& c)
         l.opt_s = off;
         if (c.optimizer == BMGD_OPT_ADAM) off += align_up(l.opt_len * 4);
     }
+    l.eval = off; off += align_up((size_t)kEvalBlocks * sizeof(double));   // partial sums of bmgd_eval_loss
     l.total = off;
     return l;
 }
@@ -724,6 +725,45 @@ BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void
     if (last) { give_event(ctx, rec.end); rec.end = last; rec.owns_end = false; }
     else HIP_TRY(ctx, hipEventRecord(rec.end, s));
     ctx->open_records.push_back(rec);
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_eval_loss(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* stream, double* host_out)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!dev_x || !dev_y || !host_out) return fail(ctx, BMGD_EINVAL, "dev_x, dev_y and host_out must not be NULL");
+    if (rows < 1 || rows >= (int64_t(1) << 30)) return fail(ctx, BMGD_EINVAL, "rows must be in [1, 2^30)");
+    if ((reinterpret_cast<uintptr_t>(dev_x) % 16) != 0 || (reinterpret_cast<uintptr_t>(dev_y) % 4) != 0)
+        return fail(ctx, BMGD_EINVAL, "device buffers must be at least 16-byte aligned");
+    const int rc = drain(ctx);
+    if (rc != BMGD_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bmgd_config& c = ctx->cfg;
+    double* partial = reinterpret_cast<double*>(static_cast<char*>(ctx->ws) + ctx->lay.eval);
+    std::vector<double> host(kEvalBlocks);
+    double total = 0.0;
+    if (c.model == BMGD_SOFTMAX) {
+        const SoftmaxDims d = softmax_dims(c.p, c.batch_n, c.n_classes);
+        const int64_t chunk = std::min<int64_t>(c.batch_n, (int64_t)kEvalBlocks * 8);
+        for (int64_t r0 = 0; r0 < rows; r0 += chunk) {
+            const int nb = (int)std::min<int64_t>(chunk, rows - r0);
+            HIP_TRY(ctx, softmax_launch_loss(static_cast<const char*>(dev_x) + (size_t)r0 * c.p * 2,
+                                             static_cast<const int32_t*>(dev_y) + r0, nb, (int)c.p, c.n_classes, ctx->wbt, ctx->u,
+                                             d, partial, s));
+            const int nblocks = (nb + 7) / 8;
+            HIP_TRY(ctx, hipMemcpyAsync(host.data(), partial, (size_t)nblocks * sizeof(double), hipMemcpyDeviceToHost, s));
+            HIP_TRY(ctx, hipStreamSynchronize(s));
+            for (int b = 0; b < nblocks; ++b) total += host[(size_t)b];
+        }
+    } else {
+        const int nblocks = (int)std::min<int64_t>(kEvalBlocks, (rows + 3) / 4);
+        HIP_TRY(ctx, glm_launch_loss(static_cast<const float*>(dev_x), static_cast<const float*>(dev_y), ctx->theta, (int)rows,
+                                     (int)c.p, c.model, partial, nblocks, s));
+        HIP_TRY(ctx, hipMemcpyAsync(host.data(), partial, (size_t)nblocks * sizeof(double), hipMemcpyDeviceToHost, s));
+        HIP_TRY(ctx, hipStreamSynchronize(s));
+        for (int b = 0; b < nblocks; ++b) total += host[(size_t)b];
+    }
+    *host_out = total / (double)rows;
     return BMGD_OK;
 }
 

@@ -115,6 +115,11 @@ hipError_t glm_launch_chain(const GlmLaunchShape& shape, const GlmArgs& args, hi
 // Step-per-launch variant: partial sums for step `args.single_step`, then reduce + update.
 hipError_t glm_launch_step(const GlmLaunchShape& shape, const GlmArgs& args, int nb, hipStream_t stream);
 
+// Evaluation: partial[b] = sum of the per-sample losses of the rows workgroup b takes (b < nblocks <= kEvalBlocks).
+constexpr int kEvalBlocks = 1024;
+hipError_t glm_launch_loss(const float* X, const float* y, const float* theta, int rows, int p, int model, double* partial,
+                           int nblocks, hipStream_t stream);
+
 // ---------------------------------------------------------------------------------------------------
 // Least squares in the form of eq. (3.1): per-mini-batch moment matrices, then a one-workgroup chain.
 
@@ -168,6 +173,10 @@ hipError_t softmax_permute_transpose(const void* X, const int32_t* perm, void* X
                                      const SoftmaxDims& d, hipStream_t stream);
 // One mini-batch update: logits, residual, gradient + update (three launches in stream order).
 hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t stream);
+// Evaluation: cross-entropy summed over `nb` rows X[row0 .. row0 + nb) (contiguous, nb <= the batch size the context
+// was created with) at the bf16 copy of W: partial[b] for b < ceil(nb / 8) workgroups.
+hipError_t softmax_launch_loss(const void* X, const int32_t* y, int nb, int p, int C, const void* WbT, float* U,
+                               const SoftmaxDims& d, double* partial, hipStream_t stream);
 // WbT <- bf16(W) transposed, whole matrix.
 hipError_t softmax_refresh_shadow(const float* W, void* WbT, int p, const SoftmaxDims& d, hipStream_t stream);
 

@@ -572,6 +572,41 @@ __global__ void __launch_bounds__(256) glm_update_kernel(float* __restrict__ the
     if (opt.kind == kOptAdam) opt.s[c] = sv;
 }
 
+// Evaluation: sum over rows of the per-sample loss at theta (least squares: (x'theta - y)^2 / 2; logistic:
+// log(1 + e^u) - y u with u = x'theta), one row per wavefront at a time, fp64 sums, one partial sum per workgroup
+// (the host adds them in index order: reproducible).
+constexpr int kLossBlock = 256;
+
+__global__ void __launch_bounds__(kLossBlock) glm_loss_kernel(const float* __restrict__ X, const float* __restrict__ y,
+                                                              const float* __restrict__ theta, int rows, int p, int model,
+                                                              double* __restrict__ partial)
+{
+    extern __shared__ __align__(16) float th[];      // [p]
+    __shared__ double wsum[kLossBlock / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int c = threadIdx.x; c < p; c += kLossBlock) th[c] = theta[c];
+    __syncthreads();
+    double acc = 0.0;
+    for (int i = blockIdx.x * (kLossBlock / 64) + wave; i < rows; i += gridDim.x * (kLossBlock / 64)) {
+        const float* row = X + (size_t)i * p;
+        float d = 0.f;
+        for (int c = lane; c < p; c += 64) d = fmaf(row[c], th[c], d);
+        const float u = group_sum(d, 64);
+        const float yi = y[i];
+        float l;
+        if (model == kLogistic) l = fmaxf(u, 0.f) + log1pf(expf(-fabsf(u))) - yi * u;
+        else l = 0.5f * (u - yi) * (u - yi);
+        acc += (double)l;
+    }
+    if (lane == 0) wsum[wave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int w = 0; w < kLossBlock / 64; ++w) t += wsum[w];
+        partial[blockIdx.x] = t;
+    }
+}
+
 using KernelFn = void (*)(GlmArgs);
 
 // Rows in flight per row slot are limited by registers: CPL * V * PF <= 16 floats per group (two groups
@@ -753,6 +788,14 @@ hipError_t glm_launch_step(const GlmLaunchShape& s, const GlmArgs& args, int nb,
     const float* part = args.partial + (size_t)(args.single_step & 1) * s.G * args.p;
     hipLaunchKernelGGL(glm_update_kernel, dim3((args.p + 255) / 256), dim3(256), 0, stream, args.theta, part,
                        args.p, s.G, args.alpha, 1.f / (float)nb, args.opt);
+    return hipGetLastError();
+}
+
+hipError_t glm_launch_loss(const float* X, const float* y, const float* theta, int rows, int p, int model, double* partial,
+                           int nblocks, hipStream_t stream)
+{
+    hipLaunchKernelGGL(glm_loss_kernel, dim3(nblocks), dim3(kLossBlock), (size_t)p * sizeof(float), stream, X, y, theta, rows, p,
+                       model, partial);
     return hipGetLastError();
 }
 

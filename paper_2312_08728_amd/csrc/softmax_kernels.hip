@@ -361,6 +361,62 @@ __global__ void __launch_bounds__(SM_THREADS) softmax_residual_kernel(const floa
     }
 }
 
+// Evaluation: cross-entropy -log softmax(u)[label] of SM_ROWS rows per workgroup from the (split) logits, one row per
+// wavefront, summed in fp64 into partial[blockIdx.x].  Not on the hot path: plain loops.
+__global__ void __launch_bounds__(SM_THREADS) softmax_loss_kernel(const float* __restrict__ U, int splits, int m_pad, int ldu,
+                                                                  const int* __restrict__ y, int nb, int C,
+                                                                  double* __restrict__ partial)
+{
+    __shared__ double wsum[SM_ROWS];
+    const int lane = threadIdx.x & 63, rr = threadIdx.x >> 6;
+    const int i = blockIdx.x * SM_ROWS + rr;
+    double l = 0.0;
+    if (i < nb) {
+        const int label = y[i];
+        float u[SM_MAXB][4];
+        float mx = -INFINITY, ul = 0.f;
+#pragma unroll
+        for (int k = 0; k < SM_MAXB; ++k) {
+            const int c = 4 * lane + 256 * k;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) u[k][v] = -INFINITY;
+            if (c < ldu) {
+                float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int sp = 0; sp < splits; ++sp) {
+                    const float4 q = *reinterpret_cast<const float4*>(U + ((size_t)sp * m_pad + i) * ldu + c);
+                    t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+                }
+                const float tv[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (c + v < C) {
+                        u[k][v] = tv[v];
+                        mx = fmaxf(mx, tv[v]);
+                        if (c + v == label) ul = tv[v];
+                    }
+            }
+        }
+        for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        float sum = 0.f;
+#pragma unroll
+        for (int k = 0; k < SM_MAXB; ++k)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sum += expf(u[k][v] - mx);
+        for (int o = 32; o >= 1; o >>= 1) {
+            sum += __shfl_xor(sum, o);
+            ul += __shfl_xor(ul, o);                 // only the lane that owns the label holds a non-zero value
+        }
+        l = (double)(mx + logf(sum) - ul);
+    }
+    if (lane == 0) wsum[rr] = l;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int q = 0; q < SM_ROWS; ++q) t += wsum[q];
+        partial[blockIdx.x] = t;
+    }
+}
+
 // WbT[c][r] = bf16(W[r][c]) for the whole matrix (after bmgd_set_theta / at creation).
 __global__ void __launch_bounds__(256) shadow_kernel(const float* __restrict__ W, unsigned short* __restrict__ WbT, int p,
                                                      int ldw, int ldwt)
@@ -492,6 +548,33 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
         hipLaunchKernelGGL((gemm_nt_kernel<true, true>), dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(256), 0, stream, h);
     else
         hipLaunchKernelGGL((gemm_nt_kernel<true, false>), dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(256), 0, stream, h);
+    return hipGetLastError();
+}
+
+hipError_t softmax_launch_loss(const void* X, const int32_t* y, int nb, int p, int C, const void* WbT, float* U,
+                               const SoftmaxDims& d, double* partial, hipStream_t stream)
+{
+    GemmArgs g{};
+    g.A = static_cast<const unsigned short*>(X);
+    g.a_idx = nullptr;
+    g.a_stride = p;
+    g.M = nb;
+    g.B = static_cast<const unsigned short*>(WbT);
+    g.b_stride = d.p_pad;
+    g.N = d.c_pad;
+    g.K = p;
+    g.k_per_split = d.k_per_split;
+    g.U = U;
+    g.ldu = d.c_pad;
+    g.m_pad = d.m_pad;
+    g.tiles_m = (nb + TM - 1) / TM;
+    g.tiles_n = d.c_pad / TN;
+    g.splits = d.splits;
+    hipLaunchKernelGGL(gemm_nt_kernel<false>, dim3((g.tiles_m * g.tiles_n * g.splits + 7) / 8 * 8), dim3(256), 0, stream, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(softmax_loss_kernel, dim3((nb + SM_ROWS - 1) / SM_ROWS), dim3(SM_THREADS), 0, stream, U, d.splits, d.m_pad,
+                       d.c_pad, y, nb, C, partial);
     return hipGetLastError();
 }
 
