@@ -19,9 +19,11 @@
  *
  * The caller owns the loops over iterations r = 1..R and buffers k = 1..K of
  * Algorithm 1: per buffer it calls bmgd_load_buffer_async() and then
- * bmgd_run_buffer().  All work is enqueued on the caller's HIP streams; only
- * bmgd_get_theta(), bmgd_get_perm(), bmgd_get_stats(), bmgd_sync() and
- * bmgd_destroy() block the host.
+ * bmgd_run_buffer().  All work is enqueued on the caller's HIP streams (plus,
+ * in BMGD_CHAIN_GRAM mode, one stream of the library's own, see below); the
+ * calls that block the host are bmgd_get_theta(), bmgd_set_theta(),
+ * bmgd_get_perm(), bmgd_get_stats(), bmgd_sync(), bmgd_eval_loss(),
+ * bmgd_set_lr_schedule(), bmgd_reset_optimizer() and bmgd_destroy().
  *
  * General rules
  *   - Every function is extern "C", never throws and never aborts.  Except for
