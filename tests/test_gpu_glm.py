@@ -269,3 +269,42 @@ def test_error_paths():
     assert B.bmgd_set_lr(c.h, 0.0) == B.BMGD_EINVAL and B.bmgd_set_lr(c.h, float('nan')) == B.BMGD_EINVAL
     assert B.bmgd_set_passes(c.h, 0) == B.BMGD_EINVAL
     c.close()
+
+
+@pytest.mark.parametrize("kw", [dict(model=wl.LINEAR, p=40, chain=0), dict(model=wl.LOGISTIC, p=200, chain=1),
+                                dict(model=wl.LINEAR, p=40, chain=3, optimizer=3)])
+def test_caller_provided_workspace(kw):
+    """Everything the context needs on the device lives in memory the caller allocates (bmgd_workspace_bytes), here a
+    torch tensor with guard bytes on both sides that must come back untouched; results equal the library-owned run."""
+    import torch
+    import paper_2312_08728_amd as B
+    model, p, chain = kw["model"], kw["p"], kw["chain"]
+    opt = kw.get("optimizer", 0)
+    w = _case(model, 4000, p, 2000, 250, T=5, R=1, alpha=0.01, x_cov="identity")
+    X, y = wl.dataset(w)
+    xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    s = torch.cuda.Stream()
+
+    def run(**extra):
+        ctx = B.Context(w.p, w.N0, w.n, w.alpha, w.T, model=model, chain=chain, optimizer=opt, **extra)
+        for k in range(2):
+            ctx.run_device_buffer(xd[k * 2000:(k + 1) * 2000], yd[k * 2000:(k + 1) * 2000], 2000, s)
+        th = ctx.get_theta()
+        ctx.close()
+        return th
+
+    cfg = B.bmgd_default_config()
+    cfg.p, cfg.buffer_n, cfg.batch_n, cfg.lr, cfg.passes = w.p, w.N0, w.n, w.alpha, w.T
+    cfg.model, cfg.chain, cfg.optimizer = model, chain, opt
+    need = B.bmgd_workspace_bytes(cfg)
+    assert need > 0 and need % 256 == 0
+    guard = 4096
+    raw = torch.full((need + 2 * guard + 256,), 0x5A, dtype=torch.uint8, device="cuda")
+    off = (-raw.data_ptr() - guard) % 256 + guard                 # 256-byte aligned start behind the front guard
+    ws = raw[off:off + need]
+    got = run(workspace=ws, workspace_bytes=need)
+    torch.cuda.synchronize()
+    assert bool((raw[:off] == 0x5A).all()) and bool((raw[off + need:] == 0x5A).all())
+    assert np.array_equal(got, run())
+    with pytest.raises(B.BmgdError):
+        B.Context(w.p, w.N0, w.n, w.alpha, w.T, model=model, chain=chain, optimizer=opt, workspace=ws, workspace_bytes=need - 256)
