@@ -42,7 +42,10 @@ struct RunRecord {                                 // event quintet of one buffe
     hipEvent_t copy_start = nullptr, copy_end = nullptr, ready = nullptr, start = nullptr, end = nullptr;
     bool has_copy = false;
     bool owns_end = true;                          // false: `end` is the stop event of the run's last chain launch
+    int n_chain = 0, n_prep = 0;                   // launches of this run with an entry in open_chain / open_prep
 };
+
+constexpr size_t kMaxOpenRuns = 4096;              // runs whose events are held before the oldest half is folded
 
 }  // namespace
 
@@ -256,10 +259,13 @@ hipEvent_t take_event(bmgd_ctx* ctx)
 
 void give_event(bmgd_ctx* ctx, hipEvent_t e) { if (e) ctx->event_pool.push_back(e); }
 
-// Fold finished runs into the running totals.  Call only after both streams have drained.
-void settle_records(bmgd_ctx* ctx)
+// Fold the oldest `count` finished runs into the running totals.  Their kernels and copies must have completed.
+void settle_records(bmgd_ctx* ctx, size_t count)
 {
-    for (RunRecord& r : ctx->open_records) {
+    count = std::min(count, ctx->open_records.size());
+    size_t n_chain = 0, n_prep = 0;
+    for (size_t i = 0; i < count; ++i) {
+        RunRecord& r = ctx->open_records[i];
         float ms = 0.f, t_ready = 0.f, t_start = 0.f, t_end = 0.f;
         const bool have_start = hipEventElapsedTime(&t_start, ctx->base, r.start) == hipSuccess;
         if (have_start && hipEventElapsedTime(&t_end, ctx->base, r.end) == hipSuccess) {
@@ -274,23 +280,46 @@ void settle_records(bmgd_ctx* ctx)
             if (hipEventElapsedTime(&t_ready, ctx->base, r.ready) == hipSuccess && have_start && t_start > t_ready)
                 ctx->wait_ms += t_start - t_ready;
         }
-        give_event(ctx, r.copy_start); give_event(ctx, r.copy_end);
-        give_event(ctx, r.ready); give_event(ctx, r.start);
-        if (r.owns_end) give_event(ctx, r.end);
+        n_chain += (size_t)r.n_chain;
+        n_prep += (size_t)r.n_prep;
     }
-    ctx->open_records.clear();
-    for (auto& pr : ctx->open_chain) {
+    // elapsed times first, hand-backs second: a run's `end` may be the stop event of its last chain launch
+    const bool all = count == ctx->open_records.size();     // then also entries of a run that failed half-way
+    n_chain = all ? ctx->open_chain.size() : std::min(n_chain, ctx->open_chain.size());
+    n_prep = all ? ctx->open_prep.size() : std::min(n_prep, ctx->open_prep.size());
+    for (size_t i = 0; i < n_chain; ++i) {
+        auto& pr = ctx->open_chain[i];
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) { ctx->chain_ms += ms; ctx->chain_launches += 1; }
         give_event(ctx, pr.first); give_event(ctx, pr.second);
     }
-    ctx->open_chain.clear();
-    for (auto& pr : ctx->open_prep) {
+    for (size_t i = 0; i < n_prep; ++i) {
+        auto& pr = ctx->open_prep[i];
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) { ctx->prep_ms += ms; ctx->prep_launches += 1; }
         give_event(ctx, pr.first); give_event(ctx, pr.second);
     }
-    ctx->open_prep.clear();
+    for (size_t i = 0; i < count; ++i) {
+        RunRecord& r = ctx->open_records[i];
+        give_event(ctx, r.copy_start); give_event(ctx, r.copy_end);
+        give_event(ctx, r.ready); give_event(ctx, r.start);
+        if (r.owns_end) give_event(ctx, r.end);
+    }
+    ctx->open_records.erase(ctx->open_records.begin(), ctx->open_records.begin() + (ptrdiff_t)count);
+    ctx->open_chain.erase(ctx->open_chain.begin(), ctx->open_chain.begin() + (ptrdiff_t)n_chain);
+    ctx->open_prep.erase(ctx->open_prep.begin(), ctx->open_prep.begin() + (ptrdiff_t)n_prep);
+}
+
+// A caller that never synchronises would otherwise pile up events without bound: once kMaxOpenRuns runs are open,
+// wait for the older half (which also keeps the host from running arbitrarily far ahead of the device) and fold it.
+// The events the next runs still wait on belong to the two latest runs, so none of them is handed back here.
+int trim_records(bmgd_ctx* ctx)
+{
+    if (ctx->open_records.size() < kMaxOpenRuns) return BMGD_OK;
+    const size_t count = ctx->open_records.size() / 2;
+    HIP_TRY(ctx, hipEventSynchronize(ctx->open_records[count - 1].end));
+    settle_records(ctx, count);
+    return BMGD_OK;
 }
 
 int drain(bmgd_ctx* ctx)
@@ -300,7 +329,7 @@ int drain(bmgd_ctx* ctx)
     if (ctx->used_compute) HIP_TRY(ctx, hipStreamSynchronize(ctx->last_compute));
     if (ctx->chain_stream) HIP_TRY(ctx, hipStreamSynchronize(ctx->chain_stream));
     ctx->chain_pending[0] = ctx->chain_pending[1] = false;
-    settle_records(ctx);
+    settle_records(ctx, ctx->open_records.size());
     unsigned flag = 0;
     HIP_TRY(ctx, hipMemcpy(&flag, ctx->sync + 1, sizeof flag, hipMemcpyDeviceToHost));
     if (flag != 0) {
@@ -484,7 +513,7 @@ void destroy_ctx(bmgd_ctx* ctx)
     if (ctx->used_copy) (void)hipStreamSynchronize(ctx->last_copy);
     if (ctx->used_compute) (void)hipStreamSynchronize(ctx->last_compute);
     if (ctx->chain_stream) (void)hipStreamSynchronize(ctx->chain_stream);
-    settle_records(ctx);
+    settle_records(ctx, ctx->open_records.size());
     if (ctx->chain_stream) (void)hipStreamDestroy(ctx->chain_stream);
     give_event(ctx, ctx->pending_copy.copy_start);
     give_event(ctx, ctx->pending_copy.copy_end);
@@ -688,6 +717,7 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
     HIP_TRY(ctx, hipStreamWaitEvent(s, slot.copy_done, 0));       // never read a slot that is still filling
     HIP_TRY(ctx, hipEventRecord(rec.start, s));
     hipEvent_t last = nullptr;
+    const size_t chain0 = ctx->open_chain.size(), prep0 = ctx->open_prep.size();
     const int rc = enqueue_compute(ctx, slot.x, slot.y, slot.rows, s, &last);
     ctx->last_compute = s;
     ctx->used_compute = true;
@@ -696,10 +726,12 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
     else HIP_TRY(ctx, hipEventRecord(rec.end, s));
     HIP_TRY(ctx, hipEventRecord(slot.compute_done, s));           // every kernel that reads the slot runs on s
     slot.was_read = true;
+    rec.n_chain = (int)(ctx->open_chain.size() - chain0);
+    rec.n_prep = (int)(ctx->open_prep.size() - prep0);
     ctx->open_records.push_back(rec);
     ctx->pending_copy = RunRecord();
     ctx->pending = -1;
-    return BMGD_OK;
+    return trim_records(ctx);
 }
 
 BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* compute_stream)
@@ -718,14 +750,17 @@ BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void
     HIP_TRY(ctx, hipEventRecord(rec.ready, s));
     HIP_TRY(ctx, hipEventRecord(rec.start, s));
     hipEvent_t last = nullptr;
+    const size_t chain0 = ctx->open_chain.size(), prep0 = ctx->open_prep.size();
     const int rc = enqueue_compute(ctx, dev_x, dev_y, rows, s, &last);
     ctx->last_compute = s;
     ctx->used_compute = true;
     if (rc != BMGD_OK) return rc;
     if (last) { give_event(ctx, rec.end); rec.end = last; rec.owns_end = false; }
     else HIP_TRY(ctx, hipEventRecord(rec.end, s));
+    rec.n_chain = (int)(ctx->open_chain.size() - chain0);
+    rec.n_prep = (int)(ctx->open_prep.size() - prep0);
     ctx->open_records.push_back(rec);
-    return BMGD_OK;
+    return trim_records(ctx);
 }
 
 BMGD_API int bmgd_eval_loss(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* stream, double* host_out)

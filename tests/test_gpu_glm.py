@@ -308,3 +308,20 @@ def test_caller_provided_workspace(kw):
     assert np.array_equal(got, run())
     with pytest.raises(B.BmgdError):
         B.Context(w.p, w.N0, w.n, w.alpha, w.T, model=model, chain=chain, optimizer=opt, workspace=ws, workspace_bytes=need - 256)
+
+
+@pytest.mark.parametrize("chain,resident", [(3, True), (1, True), (2, True), (3, False)])
+def test_ten_thousand_runs_without_a_blocking_call(chain, resident):
+    """The library folds the events of old runs by itself once some thousand are open; results and counters
+    must not depend on when that happens."""
+    w = _case(wl.LINEAR, 640, 8, 64, 16, T=1, R=1000, alpha=0.01)
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y)
+    got, st = gpu_run(w, X, y, resident=resident, chain=chain)
+    assert st.chain == chain
+    assert st.buffers_run == 10_000 and st.steps == 40_000
+    assert st.chain_launches == 10_000          # one timed launch (or chunk of launches) per run at T = 1
+    if chain == 3:
+        assert st.prep_launches == 10_000
+    assert st.compute_ms > 0 and st.chain_ms > 0
+    assert rel_l2(got, want) <= TOL
