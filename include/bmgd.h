@@ -23,7 +23,13 @@
  * in BMGD_CHAIN_GRAM mode, one stream of the library's own, see below); the
  * calls that block the host are bmgd_get_theta(), bmgd_set_theta(),
  * bmgd_get_perm(), bmgd_get_stats(), bmgd_sync(), bmgd_eval_loss(),
- * bmgd_set_lr_schedule(), bmgd_reset_optimizer() and bmgd_destroy().
+ * bmgd_set_lr_schedule(), bmgd_reset_optimizer(), bmgd_destroy() and (for
+ * part of its passes) bmgd_run_buffer_adaptive().
+ * The run calls keep a few events per buffer for the statistics; once 4096
+ * runs have been enqueued since the last blocking call, the next run call
+ * waits until the older half of them has finished and folds their timings,
+ * so a caller that never synchronises is at most some thousand buffers ahead
+ * of the device and holds a bounded number of events.
  *
  * General rules
  *   - Every function is extern "C", never throws and never aborts.  Except for
@@ -192,6 +198,21 @@ int bmgd_load_buffer_async(bmgd_ctx* ctx, const void* host_x, const void* host_y
  * PERM(seed, b, t, rows) for pass t = 1..T with b the number of buffers run before this one (or
  * PERM(seed, b mod K, 0, rows) in fixed mode).  Returns BMGD_ESTATE if nothing is loaded. */
 int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream);
+
+/* Computation step with as many passes as the buffering step leaves time for (Section 2.1: the updates on the
+ * buffer in hand go on until the next buffer has been prepared).  Starts the copy of the next buffer
+ * (next_host_x, next_host_y, next_rows: as for bmgd_load_buffer_async, on copy_stream) and makes passes
+ * t = 1, 2, ... over the loaded buffer on compute_stream, one launch per pass, until that copy has completed, but
+ * never fewer than min_passes nor more than max_passes (1 <= min_passes <= max_passes <= 2^20); the passes value
+ * of the context is not used.  The copy's completion is looked at before each pass is enqueued, with at most two
+ * passes enqueued and unfinished, so the last pass starts at most two passes after the copy has ended.
+ * *passes_done (may be NULL) receives the number of passes made: it depends on timing, and so does theta; a run
+ * of bmgd_run_buffer with that many passes gives the same theta.  On return the next buffer is the loaded one.
+ * next_host_x = next_host_y = NULL: there is no next buffer, min_passes passes are made.
+ * Blocks the host while it waits for passes to finish (all but the last two); returns BMGD_ESTATE if nothing is
+ * loaded. */
+int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const void* next_host_x, const void* next_host_y,
+                             int64_t next_rows, void* copy_stream, int min_passes, int max_passes, int* passes_done);
 
 /* Same computation step on a buffer that is already resident in device memory and owned by the caller
  * (no copy, no slot): dev_x [rows][p], dev_y [rows], 256-byte aligned, valid until the work completes. */

@@ -26,7 +26,7 @@ BMGD_OPT_SGD, BMGD_OPT_MOMENTUM, BMGD_OPT_NAG, BMGD_OPT_ADAM = 0, 1, 2, 3
 
 EXPORTS = [
     "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
-    "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_device_buffer", "bmgd_get_theta",
+    "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_buffer_adaptive", "bmgd_run_device_buffer", "bmgd_get_theta",
     "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_lr_schedule", "bmgd_reset_optimizer", "bmgd_eval_loss", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
     "bmgd_last_error", "bmgd_destroy",
 ]
@@ -70,6 +70,8 @@ def _load() -> C.CDLL:
     lib.bmgd_load_buffer_async.argtypes, lib.bmgd_load_buffer_async.restype = [vp, vp, vp, i64, vp], i32
     lib.bmgd_run_buffer.argtypes, lib.bmgd_run_buffer.restype = [vp, vp], i32
     lib.bmgd_run_device_buffer.argtypes, lib.bmgd_run_device_buffer.restype = [vp, vp, vp, i64, vp], i32
+    lib.bmgd_run_buffer_adaptive.argtypes = [vp, vp, vp, vp, i64, vp, C.c_int, C.c_int, C.POINTER(C.c_int)]
+    lib.bmgd_run_buffer_adaptive.restype = i32
     lib.bmgd_get_theta.argtypes, lib.bmgd_get_theta.restype = [vp, vp, i64], i32
     lib.bmgd_set_theta.argtypes, lib.bmgd_set_theta.restype = [vp, vp, i64], i32
     lib.bmgd_set_position.argtypes, lib.bmgd_set_position.restype = [vp, i64], i32
@@ -141,6 +143,15 @@ def bmgd_load_buffer_async(ctx, host_x, host_y, rows, copy_stream=None) -> int:
 
 def bmgd_run_buffer(ctx, compute_stream=None) -> int:
     return lib.bmgd_run_buffer(ctx, _stream(compute_stream))
+
+
+def bmgd_run_buffer_adaptive(ctx, compute_stream, next_host_x, next_host_y, next_rows, copy_stream, min_passes, max_passes):
+    done = C.c_int(0)
+    nx = _ptr(next_host_x) if next_host_x is not None else None
+    ny = _ptr(next_host_y) if next_host_y is not None else None
+    rc = lib.bmgd_run_buffer_adaptive(ctx, _stream(compute_stream), nx, ny, next_rows, _stream(copy_stream), min_passes,
+                                      max_passes, C.byref(done))
+    return rc, done.value
 
 
 def bmgd_run_device_buffer(ctx, dev_x, dev_y, rows, compute_stream=None) -> int:
@@ -244,6 +255,13 @@ class Context:
 
     def run_buffer(self, compute_stream=None):
         self._check(bmgd_run_buffer(self.h, compute_stream))
+
+    def run_buffer_adaptive(self, compute_stream, next_host_x, next_host_y, next_rows, copy_stream, min_passes, max_passes) -> int:
+        """Passes over the loaded buffer until the next one has arrived; returns the number of passes made."""
+        rc, done = bmgd_run_buffer_adaptive(self.h, compute_stream, next_host_x, next_host_y, next_rows, copy_stream,
+                                            min_passes, max_passes)
+        self._check(rc)
+        return done
 
     def run_device_buffer(self, dev_x, dev_y, rows, compute_stream=None):
         self._check(bmgd_run_device_buffer(self.h, dev_x, dev_y, rows, compute_stream))

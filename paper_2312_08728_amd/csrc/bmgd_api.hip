@@ -363,10 +363,13 @@ float rate_of(const bmgd_ctx* ctx, int64_t ahead)
     return ctx->lr_tab_host[(size_t)u];
 }
 
-// Enqueue T passes over (x, y, rows) on `stream`.
-// *end_event receives the stop event of the run's last kernel if that kernel carries one (and then runs on the
-// library's chain stream), else NULL: then the run ends with the last work enqueued on `stream`.
-int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hipStream_t stream, hipEvent_t* end_event)
+// Enqueue passes t = first + 1 .. first + count over (x, y, rows) on `stream`, at most kMaxPassesPerLaunch per launch.
+// *end_event receives the stop event of the last kernel if that kernel carries one (and then runs on the
+// library's chain stream), else NULL: then the passes end with the last work enqueued on `stream`.
+// *chunk_end (may be NULL) receives an event that completes when the last of these passes has: it stays valid until
+// the run's records are settled.
+int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hipStream_t stream, int first, int count,
+                   hipEvent_t* end_event, hipEvent_t* chunk_end)
 {
     *end_event = nullptr;
     const bmgd_config& c = ctx->cfg;
@@ -377,8 +380,8 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
     const long long ticks = (c.barrier_timeout_us > 0 ? c.barrier_timeout_us : 2000000) * 100LL;
     const int lr_len = (int)ctx->lr_tab_host.size();
 
-    for (int t0 = 0; t0 < c.passes; t0 += kMaxPassesPerLaunch) {
-        const int np = std::min(kMaxPassesPerLaunch, c.passes - t0);
+    for (int t0 = first; t0 < first + count; t0 += kMaxPassesPerLaunch) {
+        const int np = std::min(kMaxPassesPerLaunch, first + count - t0);
         PermKeys keys{};
         const int nperm = fixed ? 1 : np;
         for (int i = 0; i < nperm; ++i) perm_round_keys(c.seed, b, fixed ? 0u : (uint32_t)(t0 + i + 1), keys.key[i]);
@@ -409,6 +412,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
             ctx->chain_pending[i] = true;
             ctx->open_chain.emplace_back(ev0, ev1);
             *end_event = ev1;
+            if (chunk_end) *chunk_end = ev1;
             continue;
         }
         if (!fixed || t0 == 0) HIP_TRY(ctx, launch_perm(ctx->perm, rows, nperm, keys, stream));
@@ -442,6 +446,7 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
             }
             HIP_TRY(ctx, hipEventRecord(ev1, stream));
             ctx->open_chain.emplace_back(ev0, ev1);
+            if (chunk_end) *chunk_end = ev1;
             ctx->lr_pos += (int64_t)np * M;
             ctx->opt_k += (int64_t)np * M;
             continue;
@@ -497,13 +502,28 @@ int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, h
         }
         HIP_TRY(ctx, hipEventRecord(ev1, stream));
         ctx->open_chain.emplace_back(ev0, ev1);
+        if (chunk_end) *chunk_end = ev1;
         ctx->lr_pos += (int64_t)np * M;
         ctx->opt_k += (int64_t)np * M;
     }
-    ctx->steps += (int64_t)c.passes * M;
-    ctx->sample_gradients += (int64_t)c.passes * rows;
-    ctx->buffer_counter += 1;
     return BMGD_OK;
+}
+
+// Bookkeeping at the end of a run of `passes` passes over a buffer of `rows` rows.
+void finish_run(bmgd_ctx* ctx, int64_t rows, int64_t passes)
+{
+    const int64_t n = std::min<int64_t>(ctx->cfg.batch_n, rows);
+    ctx->steps += passes * batches_of(rows, n);
+    ctx->sample_gradients += passes * rows;
+    ctx->buffer_counter += 1;
+}
+
+// Enqueue the T passes of Algorithm 1 over (x, y, rows).
+int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hipStream_t stream, hipEvent_t* end_event)
+{
+    const int rc = enqueue_passes(ctx, x, y, rows, stream, 0, ctx->cfg.passes, end_event, nullptr);
+    if (rc == BMGD_OK) finish_run(ctx, rows, ctx->cfg.passes);
+    return rc;
 }
 
 void destroy_ctx(bmgd_ctx* ctx)
@@ -672,18 +692,13 @@ BMGD_API bmgd_ctx* bmgd_create(int64_t p, int64_t buffer_n, int64_t batch_n, dou
     return ctx;
 }
 
-BMGD_API int bmgd_load_buffer_async(bmgd_ctx* ctx, const void* host_x, const void* host_y, int64_t rows, void* copy_stream)
+// Copy (host_x, host_y) into the slot the next load goes to; `rec` receives the copy's events.
+static int enqueue_load(bmgd_ctx* ctx, const void* host_x, const void* host_y, int64_t rows, hipStream_t cs, RunRecord& rec,
+                        int* slot_out)
 {
-    if (!ctx) return BMGD_EINVAL;
-    if (!host_x || !host_y) return fail(ctx, BMGD_EINVAL, "host_x and host_y must not be NULL");
-    if (rows < 1 || rows > ctx->cfg.buffer_n) return fail(ctx, BMGD_EINVAL, "rows must be in [1, buffer_n]");
-    if (ctx->pending >= 0) return fail(ctx, BMGD_ESTATE, "a buffer is already loaded and has not been run");
-    HIP_TRY(ctx, hipSetDevice(ctx->device));
-    hipStream_t cs = static_cast<hipStream_t>(copy_stream);
     Slot& slot = ctx->slots[ctx->next_slot];
     // the copy must not overwrite rows a run is still reading
     if (slot.was_read) HIP_TRY(ctx, hipStreamWaitEvent(cs, slot.compute_done, 0));
-    RunRecord& rec = ctx->pending_copy;
     if (!rec.copy_start) rec.copy_start = take_event(ctx);
     if (!rec.copy_end) rec.copy_end = take_event(ctx);
     if (!rec.copy_start || !rec.copy_end) return fail(ctx, BMGD_EHIP, "could not create events");
@@ -696,10 +711,24 @@ BMGD_API int bmgd_load_buffer_async(bmgd_ctx* ctx, const void* host_x, const voi
     rec.has_copy = true;
     slot.rows = rows;
     ctx->h2d_bytes += (int64_t)(xbytes + ybytes);
-    ctx->pending = ctx->next_slot;
+    *slot_out = ctx->next_slot;
     ctx->next_slot ^= 1;
     ctx->last_copy = cs;
     ctx->used_copy = true;
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_load_buffer_async(bmgd_ctx* ctx, const void* host_x, const void* host_y, int64_t rows, void* copy_stream)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!host_x || !host_y) return fail(ctx, BMGD_EINVAL, "host_x and host_y must not be NULL");
+    if (rows < 1 || rows > ctx->cfg.buffer_n) return fail(ctx, BMGD_EINVAL, "rows must be in [1, buffer_n]");
+    if (ctx->pending >= 0) return fail(ctx, BMGD_ESTATE, "a buffer is already loaded and has not been run");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    int slot = -1;
+    const int rc = enqueue_load(ctx, host_x, host_y, rows, static_cast<hipStream_t>(copy_stream), ctx->pending_copy, &slot);
+    if (rc != BMGD_OK) return rc;
+    ctx->pending = slot;
     return BMGD_OK;
 }
 
@@ -731,6 +760,75 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
     ctx->open_records.push_back(rec);
     ctx->pending_copy = RunRecord();
     ctx->pending = -1;
+    return trim_records(ctx);
+}
+
+BMGD_API int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const void* next_host_x, const void* next_host_y,
+                                      int64_t next_rows, void* copy_stream, int min_passes, int max_passes, int* passes_done)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (passes_done) *passes_done = 0;
+    if (ctx->pending < 0) return fail(ctx, BMGD_ESTATE, "no buffer is loaded");
+    if (min_passes < 1 || max_passes < min_passes || max_passes > (1 << 20))
+        return fail(ctx, BMGD_EINVAL, "need 1 <= min_passes <= max_passes <= 2^20");
+    const bool have_next = next_host_x != nullptr || next_host_y != nullptr;
+    if (have_next && (!next_host_x || !next_host_y)) return fail(ctx, BMGD_EINVAL, "next_host_x and next_host_y go together");
+    if (have_next && (next_rows < 1 || next_rows > ctx->cfg.buffer_n))
+        return fail(ctx, BMGD_EINVAL, "next_rows must be in [1, buffer_n]");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = static_cast<hipStream_t>(compute_stream);
+    Slot& slot = ctx->slots[ctx->pending];
+    RunRecord rec = ctx->pending_copy;
+    ctx->pending_copy = RunRecord();
+    rec.ready = take_event(ctx); rec.start = take_event(ctx); rec.end = take_event(ctx);
+    if (!rec.ready || !rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
+    HIP_TRY(ctx, hipEventRecord(rec.ready, s));
+    HIP_TRY(ctx, hipStreamWaitEvent(s, slot.copy_done, 0));
+    HIP_TRY(ctx, hipEventRecord(rec.start, s));
+    const size_t chain0 = ctx->open_chain.size(), prep0 = ctx->open_prep.size();
+    ctx->last_compute = s;
+    ctx->used_compute = true;
+
+    // the buffering step for the next buffer, into the other slot (Section 2.1: both steps at the same time)
+    RunRecord next_rec;
+    int next_slot = -1;
+    if (have_next) {
+        const int rc = enqueue_load(ctx, next_host_x, next_host_y, next_rows, static_cast<hipStream_t>(copy_stream), next_rec,
+                                    &next_slot);
+        if (rc != BMGD_OK) return rc;
+    }
+
+    // One pass per launch; at most two passes enqueued and unfinished, so that the decision to stop lags the arrival
+    // of the next buffer by at most two passes and the device still never runs dry.
+    int passes = 0;
+    hipEvent_t last = nullptr, in_flight[2] = {nullptr, nullptr};
+    for (;;) {
+        if (passes >= max_passes) break;
+        if (passes >= min_passes) {
+            if (!have_next) break;
+            const hipError_t q = hipEventQuery(next_rec.copy_end);
+            if (q == hipSuccess) break;
+            if (q != hipErrorNotReady) return hip_fail(ctx, q, "hipEventQuery(copy of the next buffer)");
+        }
+        if (in_flight[0]) HIP_TRY(ctx, hipEventSynchronize(in_flight[0]));
+        hipEvent_t chunk = nullptr;
+        const int rc = enqueue_passes(ctx, slot.x, slot.y, slot.rows, s, passes, 1, &last, &chunk);
+        if (rc != BMGD_OK) return rc;
+        in_flight[0] = in_flight[1];
+        in_flight[1] = chunk;
+        passes += 1;
+    }
+    finish_run(ctx, slot.rows, passes);
+    if (last) { give_event(ctx, rec.end); rec.end = last; rec.owns_end = false; }
+    else HIP_TRY(ctx, hipEventRecord(rec.end, s));
+    HIP_TRY(ctx, hipEventRecord(slot.compute_done, s));
+    slot.was_read = true;
+    rec.n_chain = (int)(ctx->open_chain.size() - chain0);
+    rec.n_prep = (int)(ctx->open_prep.size() - prep0);
+    ctx->open_records.push_back(rec);
+    ctx->pending = next_slot;
+    ctx->pending_copy = next_rec;
+    if (passes_done) *passes_done = passes;
     return trim_records(ctx);
 }
 
