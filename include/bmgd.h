@@ -40,7 +40,12 @@
  *   - "host" pointers are ordinary or pinned host memory, "device" pointers are
  *     HIP device memory on the context's device.  Streams are hipStream_t
  *     values passed as void* (NULL = the default stream).  Keep all streams at
- *     the default priority.
+ *     the default priority.  HIP spreads a process's streams over a few
+ *     hardware queues (four by default) and work on streams that share a queue
+ *     runs one after the other, copies included: a process that wants the copy
+ *     of one buffer to overlap the computation on another keeps the number of
+ *     streams it uses small (default stream, one copy stream, one compute
+ *     stream, the library's chain stream) and reuses them.
  *   - If no usable GPU is present every call that needs one fails with
  *     BMGD_EHIP; there is no CPU fallback.
  */
@@ -146,9 +151,9 @@ typedef struct bmgd_stats {
     int64_t h2d_bytes;         /* bytes handed to host->device copies by bmgd_load_buffer_async */
     double  copy_ms;           /* device time spent in those copies (event-timed, completed ones) */
     double  compute_ms;        /* device time spent in bmgd_run_* work (event-timed, completed ones) */
-    double  wait_ms;           /* part of copy time that compute had to wait for: sum over runs of the
-                                  time between "previous run finished (or this run was enqueued)" and
-                                  "this run's buffer finished loading", when positive */
+    double  wait_ms;           /* part of copy_ms that was not overlapped by compute: sum over runs of the part of
+                                  the run's copy that came after every earlier run had finished.
+                                  1 - wait_ms / copy_ms = fraction of the host->device time that was hidden */
     int32_t n_workgroups;      /* launch shape in use */
     int32_t threads_per_group;
     int32_t chain;             /* resolved BMGD_CHAIN_* */

@@ -38,8 +38,8 @@ struct Slot {
     bool was_read = false;
 };
 
-struct RunRecord {                                 // event quintet of one buffer, for the overlap statistics
-    hipEvent_t copy_start = nullptr, copy_end = nullptr, ready = nullptr, start = nullptr, end = nullptr;
+struct RunRecord {                                 // events of one buffer, for the overlap statistics
+    hipEvent_t copy_start = nullptr, copy_end = nullptr, start = nullptr, end = nullptr;
     bool has_copy = false;
     bool owns_end = true;                          // false: `end` is the stop event of the run's last chain launch
     int n_chain = 0, n_prep = 0;                   // launches of this run with an entry in open_chain / open_prep
@@ -266,19 +266,20 @@ void settle_records(bmgd_ctx* ctx, size_t count)
     size_t n_chain = 0, n_prep = 0;
     for (size_t i = 0; i < count; ++i) {
         RunRecord& r = ctx->open_records[i];
-        float ms = 0.f, t_ready = 0.f, t_start = 0.f, t_end = 0.f;
-        const bool have_start = hipEventElapsedTime(&t_start, ctx->base, r.start) == hipSuccess;
-        if (have_start && hipEventElapsedTime(&t_end, ctx->base, r.end) == hipSuccess) {
+        float t_start = 0.f, t_end = 0.f, c_start = 0.f, c_end = 0.f;
+        // the part of this buffer's copy during which no earlier run was computing: copy time that was not hidden
+        if (r.has_copy && hipEventElapsedTime(&c_start, ctx->base, r.copy_start) == hipSuccess &&
+            hipEventElapsedTime(&c_end, ctx->base, r.copy_end) == hipSuccess && c_end > c_start) {
+            ctx->copy_ms += c_end - c_start;
+            const double from = std::max<double>(c_start, ctx->busy_until);
+            if (c_end > from) ctx->wait_ms += c_end - from;
+        }
+        if (hipEventElapsedTime(&t_start, ctx->base, r.start) == hipSuccess &&
+            hipEventElapsedTime(&t_end, ctx->base, r.end) == hipSuccess) {
             // runs may overlap (the pre-pass of one with the chain of the one before): count the union
             const double from = std::max<double>(t_start, ctx->busy_until);
             if (t_end > from) ctx->compute_ms += t_end - from;
             ctx->busy_until = std::max<double>(ctx->busy_until, t_end);
-        }
-        if (r.has_copy) {
-            if (hipEventElapsedTime(&ms, r.copy_start, r.copy_end) == hipSuccess) ctx->copy_ms += ms;
-            // time the compute stream sat at "buffer not loaded yet"
-            if (hipEventElapsedTime(&t_ready, ctx->base, r.ready) == hipSuccess && have_start && t_start > t_ready)
-                ctx->wait_ms += t_start - t_ready;
         }
         n_chain += (size_t)r.n_chain;
         n_prep += (size_t)r.n_prep;
@@ -302,7 +303,7 @@ void settle_records(bmgd_ctx* ctx, size_t count)
     for (size_t i = 0; i < count; ++i) {
         RunRecord& r = ctx->open_records[i];
         give_event(ctx, r.copy_start); give_event(ctx, r.copy_end);
-        give_event(ctx, r.ready); give_event(ctx, r.start);
+        give_event(ctx, r.start);
         if (r.owns_end) give_event(ctx, r.end);
     }
     ctx->open_records.erase(ctx->open_records.begin(), ctx->open_records.begin() + (ptrdiff_t)count);
@@ -740,9 +741,8 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
     hipStream_t s = static_cast<hipStream_t>(compute_stream);
     Slot& slot = ctx->slots[ctx->pending];
     RunRecord rec = ctx->pending_copy;
-    rec.ready = take_event(ctx); rec.start = take_event(ctx); rec.end = take_event(ctx);
-    if (!rec.ready || !rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
-    HIP_TRY(ctx, hipEventRecord(rec.ready, s));
+    rec.start = take_event(ctx); rec.end = take_event(ctx);
+    if (!rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
     HIP_TRY(ctx, hipStreamWaitEvent(s, slot.copy_done, 0));       // never read a slot that is still filling
     HIP_TRY(ctx, hipEventRecord(rec.start, s));
     hipEvent_t last = nullptr;
@@ -780,9 +780,8 @@ BMGD_API int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const
     Slot& slot = ctx->slots[ctx->pending];
     RunRecord rec = ctx->pending_copy;
     ctx->pending_copy = RunRecord();
-    rec.ready = take_event(ctx); rec.start = take_event(ctx); rec.end = take_event(ctx);
-    if (!rec.ready || !rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
-    HIP_TRY(ctx, hipEventRecord(rec.ready, s));
+    rec.start = take_event(ctx); rec.end = take_event(ctx);
+    if (!rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
     HIP_TRY(ctx, hipStreamWaitEvent(s, slot.copy_done, 0));
     HIP_TRY(ctx, hipEventRecord(rec.start, s));
     const size_t chain0 = ctx->open_chain.size(), prep0 = ctx->open_prep.size();
@@ -843,9 +842,8 @@ BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t s = static_cast<hipStream_t>(compute_stream);
     RunRecord rec;
-    rec.ready = take_event(ctx); rec.start = take_event(ctx); rec.end = take_event(ctx);
-    if (!rec.ready || !rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
-    HIP_TRY(ctx, hipEventRecord(rec.ready, s));
+    rec.start = take_event(ctx); rec.end = take_event(ctx);
+    if (!rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
     HIP_TRY(ctx, hipEventRecord(rec.start, s));
     hipEvent_t last = nullptr;
     const size_t chain0 = ctx->open_chain.size(), prep0 = ctx->open_prep.size();
