@@ -98,6 +98,22 @@ def test_wide_rows_grids_and_chain_modes():
             assert rel_l2(got, want) <= TOL, (p, G, chain)
 
 
+@pytest.mark.parametrize("model,p,n,G", [(wl.LINEAR, 4096, 1000, 5), (wl.LOGISTIC, 4096, 700, 24), (wl.LINEAR, 2052, 900, 40),
+                                         (wl.LOGISTIC, 1028, 512, 0), (wl.LINEAR, 3000, 333, 2)])
+def test_wide_rows_two_rows_in_flight(model, p, n, G):
+    """Wide rows over several workgroups: the kernel that keeps two rows per wavefront in flight.  Odd and even numbers
+    of row groups per step (a step then ends on either register set), one group per step, a ragged last batch, several
+    passes and buffers, columns that do not fill the last chunk."""
+    w = _case(model, 5000, p, 2500, n, T=2, R=2, alpha=(0.2 / p) if model == wl.LINEAR else 0.05, x_cov="identity")
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y)
+    got, st = gpu_run(w, X, y, n_workgroups=G, chain=1)
+    assert st.threads_per_group == 512 and st.n_workgroups > 1
+    assert rel_l2(got, want) <= TOL, (p, n, st.n_workgroups)
+    again, _ = gpu_run(w, X, y, n_workgroups=G, chain=1, resident=True)
+    assert np.array_equal(got, again)
+
+
 def test_edge_cases():
     for N, N0, n in [(1, 1, 1), (5, 5, 8), (64, 64, 64), (65, 64, 64), (1000, 1000, 1000), (999, 500, 1)]:
         w = _case(wl.LINEAR, N, 6, N0, min(n, N0), T=3, R=2, alpha=0.05, x_cov="identity")
@@ -183,7 +199,7 @@ def test_schedules_of_learning_rate_and_passes():
 
 
 @pytest.mark.parametrize("model,p,n,chain", [(wl.LOGISTIC, 40, 250, 1), (wl.LOGISTIC, 200, 512, 1), (wl.LINEAR, 1024, 500, 1),
-                                             (wl.LINEAR, 40, 250, 3), (wl.LINEAR, 100, 300, 3), (wl.LOGISTIC, 40, 250, 2)])
+                                             (wl.LINEAR, 2304, 600, 1), (wl.LINEAR, 40, 250, 3), (wl.LINEAR, 100, 300, 3), (wl.LOGISTIC, 40, 250, 2)])
 def test_learning_rate_per_update(model, p, n, chain):
     """A cosine table of learning rates over the updates of the whole run (Section 4.3), shorter than the run so that
     its last value has to persist, crossing passes, launches (T = 5 > 4 passes per launch) and buffers; then cleared."""

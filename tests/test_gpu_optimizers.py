@@ -39,7 +39,8 @@ def _run_both(w, X, y, kind, chain, rate, n_workgroups=0, buffers=3, reset_after
 # (model, p, n, chain, workgroups): row form with one workgroup, redundant reduction, sliced reduction (narrow and wide
 # rows), step per launch; moment form for two thread layouts
 CASES = [(wl.LOGISTIC, 40, 250, 1, 1), (wl.LOGISTIC, 40, 250, 1, 8), (wl.LOGISTIC, 200, 512, 1, 64),
-         (wl.LINEAR, 1024, 500, 1, 0), (wl.LOGISTIC, 40, 250, 2, 16), (wl.LINEAR, 40, 250, 3, 0), (wl.LINEAR, 100, 300, 3, 0)]
+         (wl.LINEAR, 1024, 500, 1, 0), (wl.LINEAR, 2304, 500, 1, 0), (wl.LOGISTIC, 4096, 700, 1, 40),
+         (wl.LOGISTIC, 40, 250, 2, 16), (wl.LINEAR, 40, 250, 3, 0), (wl.LINEAR, 100, 300, 3, 0)]
 
 
 @pytest.mark.parametrize("kind", KINDS)
