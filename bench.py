@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
 # HBM traffic of one launch of the chain kernel on the primary workload, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE (see profiles/); only valid for the kernel source it was measured on.
-TRAFFIC = {"cfg2": {"kernel_sha256": "aa0950e8785d378071d84f7b28c078e8102dd81c98d570148c2c12b4690f229e", "bytes_per_launch": 178923765}}
+TRAFFIC = {"cfg2": {"kernel_sha256": "0777741f55161e3b7ac2b7d92c9bca11fd6f923425a1ce36f6c27165f3c644ed", "bytes_per_launch": 178919863}}
 
 
 def _kernel_sha() -> str:
@@ -155,7 +155,9 @@ def _roofline(w, delta, traffic=None):
     achieved = bytes_per_launch / per_launch_s / 1e9
     return {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
-            "kernel": "glm_chain_kernel", "avg_launch_ms": round(per_launch_s * 1e3, 4),
+            # rows wider than 1024 floats on more than one workgroup run the two-rows-in-flight variant
+            "kernel": "glm_wide_kernel" if w.p > 1024 and w.p % 4 == 0 and delta["n_workgroups"] > 1 else "glm_chain_kernel",
+            "avg_launch_ms": round(per_launch_s * 1e3, 4),
             "algorithmic_bytes_per_launch": int(bytes_per_launch)}
 
 
