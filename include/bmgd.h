@@ -219,6 +219,50 @@ int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream);
 int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const void* next_host_x, const void* next_host_y,
                              int64_t next_rows, void* copy_stream, int min_passes, int max_passes, int* passes_done);
 
+/* ---- Reading buffers from storage (the first of the two transfers of Section 2.1) -----------------------------
+ * A reader owns a host thread that reads consecutive buffers of a data set from two flat files into a ring of
+ * pinned host buffers, ahead of the consumer, so that bmgd_load_buffer_async() always finds its next buffer in
+ * memory and the copy to the device can overlap both the reading and the computation.
+ *   x_path   row-major [n_rows][p] fp32 or bf16 (x_dtype), no header
+ *   y_path   [n_rows] 4-byte items (fp32 responses or int32 class ids), no header
+ * Buffer k is rows [k buffer_n, min((k + 1) buffer_n, n_rows)); buffers are delivered in file order, and again from
+ * the start after the last one if loop != 0 (iterations r = 1, 2, ... of Algorithm 1).  ring_slots in [2, 64] pinned
+ * buffers of buffer_n rows are allocated.  Must be called with the device current on which the contexts it feeds
+ * live.  Errors: BMGD_EINVAL (arguments, missing or short file), BMGD_EHIP, BMGD_ENOMEM; message from
+ * bmgd_reader_last_error(NULL) for a failed open (per calling thread), else from the reader. */
+typedef struct bmgd_reader bmgd_reader;
+int bmgd_reader_open(const char* x_path, const char* y_path, int64_t p, int32_t x_dtype, int64_t n_rows,
+                     int64_t buffer_n, int32_t ring_slots, int32_t loop, bmgd_reader** out);
+
+/* Blocks until the next buffer is in memory and hands it out: *host_x, *host_y point into the ring (pinned; owned by
+ * the reader), *rows is its row count.  *rows = 0 with BMGD_OK: the data set has been delivered completely
+ * (loop = 0).  BMGD_ESTATE if every slot is handed out; BMGD_EINVAL if reading failed (see bmgd_reader_last_error). */
+int bmgd_reader_acquire(bmgd_reader* r, const void** host_x, const void** host_y, int64_t* rows);
+
+/* Hands back the oldest buffer that is handed out.  after_stream != 0: the reader refills it only once everything
+ * enqueued on copy_stream up to now has completed (call it right after enqueueing the copy out of the buffer);
+ * after_stream = 0: it may be refilled at once. */
+int bmgd_reader_release(bmgd_reader* r, void* copy_stream, int32_t after_stream);
+
+/* bmgd_reader_acquire + bmgd_load_buffer_async + bmgd_reader_release(after the copy) in one call.  *rows_out = rows
+ * of the buffer now loaded, 0 at the end of the data (then nothing was loaded). */
+int bmgd_load_from_reader(bmgd_ctx* ctx, bmgd_reader* r, void* copy_stream, int64_t* rows_out);
+
+/* bmgd_run_buffer_adaptive with the next buffer taken from a reader: before every pass the reader is asked (without
+ * blocking) whether its next buffer is in host memory; as soon as it is, its copy to the device starts (and the ring
+ * slot is handed back behind that copy), and the passes go on until the copy has completed.  So the device keeps
+ * working through both transfers of Section 2.1.  *next_rows (may be NULL) receives the rows of the buffer that is
+ * loaded on return, 0 if the data set has been delivered completely (loop = 0): then nothing is loaded.  If
+ * max_passes is reached before the reader has the buffer, the call waits for it and starts its copy before returning. */
+int bmgd_run_buffer_adaptive_reader(bmgd_ctx* ctx, void* compute_stream, bmgd_reader* reader, void* copy_stream,
+                                    int min_passes, int max_passes, int* passes_done, int64_t* next_rows);
+
+/* Bytes read from the files so far and the time the reading thread spent inside read calls. */
+int bmgd_reader_stats(bmgd_reader* r, int64_t* bytes_read, double* read_seconds);
+const char* bmgd_reader_last_error(bmgd_reader* r);
+/* Stops the thread, waits for copies out of the ring that the reader was told about, frees the ring. */
+void bmgd_reader_close(bmgd_reader* r);
+
 /* Same computation step on a buffer that is already resident in device memory and owned by the caller
  * (no copy, no slot): dev_x [rows][p], dev_y [rows], 256-byte aligned, valid until the work completes. */
 int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows,

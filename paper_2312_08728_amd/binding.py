@@ -26,6 +26,8 @@ BMGD_OPT_SGD, BMGD_OPT_MOMENTUM, BMGD_OPT_NAG, BMGD_OPT_ADAM = 0, 1, 2, 3
 
 EXPORTS = [
     "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
+    "bmgd_reader_open", "bmgd_reader_acquire", "bmgd_reader_release", "bmgd_load_from_reader", "bmgd_run_buffer_adaptive_reader", "bmgd_reader_stats",
+    "bmgd_reader_last_error", "bmgd_reader_close",
     "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_buffer_adaptive", "bmgd_run_device_buffer", "bmgd_get_theta",
     "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_lr_schedule", "bmgd_reset_optimizer", "bmgd_eval_loss", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
     "bmgd_last_error", "bmgd_destroy",
@@ -72,6 +74,16 @@ def _load() -> C.CDLL:
     lib.bmgd_run_device_buffer.argtypes, lib.bmgd_run_device_buffer.restype = [vp, vp, vp, i64, vp], i32
     lib.bmgd_run_buffer_adaptive.argtypes = [vp, vp, vp, vp, i64, vp, C.c_int, C.c_int, C.POINTER(C.c_int)]
     lib.bmgd_run_buffer_adaptive.restype = i32
+    lib.bmgd_reader_open.argtypes = [C.c_char_p, C.c_char_p, i64, i32, i64, i64, i32, i32, C.POINTER(vp)]
+    lib.bmgd_reader_open.restype = i32
+    lib.bmgd_reader_acquire.argtypes, lib.bmgd_reader_acquire.restype = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(i64)], i32
+    lib.bmgd_reader_release.argtypes, lib.bmgd_reader_release.restype = [vp, vp, i32], i32
+    lib.bmgd_load_from_reader.argtypes, lib.bmgd_load_from_reader.restype = [vp, vp, vp, C.POINTER(i64)], i32
+    lib.bmgd_run_buffer_adaptive_reader.argtypes = [vp, vp, vp, vp, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(i64)]
+    lib.bmgd_run_buffer_adaptive_reader.restype = i32
+    lib.bmgd_reader_stats.argtypes, lib.bmgd_reader_stats.restype = [vp, C.POINTER(i64), C.POINTER(C.c_double)], i32
+    lib.bmgd_reader_last_error.argtypes, lib.bmgd_reader_last_error.restype = [vp], C.c_char_p
+    lib.bmgd_reader_close.argtypes, lib.bmgd_reader_close.restype = [vp], None
     lib.bmgd_get_theta.argtypes, lib.bmgd_get_theta.restype = [vp, vp, i64], i32
     lib.bmgd_set_theta.argtypes, lib.bmgd_set_theta.restype = [vp, vp, i64], i32
     lib.bmgd_set_position.argtypes, lib.bmgd_set_position.restype = [vp, i64], i32
@@ -222,6 +234,103 @@ class BmgdError(RuntimeError):
         self.code = code
 
 
+def bmgd_reader_open(x_path, y_path, p, x_dtype, n_rows, buffer_n, ring_slots, loop):
+    h = C.c_void_p()
+    rc = lib.bmgd_reader_open(os.fsencode(x_path), os.fsencode(y_path), p, x_dtype, n_rows, buffer_n, ring_slots,
+                              1 if loop else 0, C.byref(h))
+    return rc, (h if rc == BMGD_OK else None)
+
+
+def bmgd_reader_acquire(reader):
+    x, y, rows = C.c_void_p(), C.c_void_p(), C.c_int64()
+    rc = lib.bmgd_reader_acquire(reader, C.byref(x), C.byref(y), C.byref(rows))
+    return rc, x.value, y.value, rows.value
+
+
+def bmgd_reader_release(reader, copy_stream=None, after_stream=True) -> int:
+    return lib.bmgd_reader_release(reader, _stream(copy_stream), 1 if after_stream else 0)
+
+
+def bmgd_load_from_reader(ctx, reader, copy_stream=None):
+    rows = C.c_int64()
+    rc = lib.bmgd_load_from_reader(ctx, reader, _stream(copy_stream), C.byref(rows))
+    return rc, rows.value
+
+
+def bmgd_run_buffer_adaptive_reader(ctx, compute_stream, reader, copy_stream, min_passes, max_passes):
+    done, rows = C.c_int(0), C.c_int64(0)
+    rc = lib.bmgd_run_buffer_adaptive_reader(ctx, _stream(compute_stream), reader, _stream(copy_stream), min_passes,
+                                             max_passes, C.byref(done), C.byref(rows))
+    return rc, done.value, rows.value
+
+
+def bmgd_reader_stats(reader):
+    b, t = C.c_int64(), C.c_double()
+    rc = lib.bmgd_reader_stats(reader, C.byref(b), C.byref(t))
+    return rc, b.value, t.value
+
+
+def bmgd_reader_last_error(reader=None) -> str:
+    msg = lib.bmgd_reader_last_error(reader)
+    return msg.decode() if msg else ""
+
+
+def bmgd_reader_close(reader) -> None:
+    lib.bmgd_reader_close(reader)
+
+
+class Reader:
+    """Host thread that reads buffers of a data set from two flat files into a ring of pinned buffers (bmgd_reader_*)."""
+
+    def __init__(self, x_path, y_path, p, n_rows, buffer_n, x_dtype=BMGD_F32, ring_slots=3, loop=False):
+        rc, h = bmgd_reader_open(x_path, y_path, p, x_dtype, n_rows, buffer_n, ring_slots, loop)
+        if rc != BMGD_OK:
+            raise BmgdError(rc, bmgd_reader_last_error(None))
+        self.h = h
+
+    def _check(self, rc):
+        if rc != BMGD_OK:
+            raise BmgdError(rc, bmgd_reader_last_error(self.h))
+
+    def acquire(self):
+        """(address of x, address of y, rows) of the next buffer; rows = 0 at the end of the data."""
+        rc, x, y, rows = bmgd_reader_acquire(self.h)
+        self._check(rc)
+        return x, y, rows
+
+    def release(self, copy_stream=None, after_stream=True):
+        self._check(bmgd_reader_release(self.h, copy_stream, after_stream))
+
+    def load_into(self, ctx: "Context", copy_stream=None) -> int:
+        """Next buffer into ctx's idle slot (bmgd_load_from_reader); returns its rows, 0 at the end of the data."""
+        rc, rows = bmgd_load_from_reader(ctx.h, self.h, copy_stream)
+        if rc != BMGD_OK:
+            raise BmgdError(rc, bmgd_last_error(ctx.h) or bmgd_reader_last_error(self.h))
+        return rows
+
+    def stats(self):
+        rc, b, t = bmgd_reader_stats(self.h)
+        self._check(rc)
+        return b, t
+
+    def close(self):
+        if getattr(self, "h", None):
+            bmgd_reader_close(self.h)
+            self.h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 class Context:
     """Owns one bmgd_ctx*; raises BmgdError on any non-OK status."""
 
@@ -262,6 +371,14 @@ class Context:
                                             min_passes, max_passes)
         self._check(rc)
         return done
+
+    def run_buffer_adaptive_reader(self, compute_stream, reader, copy_stream, min_passes, max_passes):
+        """Like run_buffer_adaptive with the next buffer taken from `reader`; returns (passes made, rows of the buffer now
+        loaded or 0 at the end of the data)."""
+        rc, done, rows = bmgd_run_buffer_adaptive_reader(self.h, compute_stream, reader.h, copy_stream, min_passes, max_passes)
+        if rc != BMGD_OK:
+            raise BmgdError(rc, bmgd_last_error(self.h))
+        return done, rows
 
     def run_device_buffer(self, dev_x, dev_y, rows, compute_stream=None):
         self._check(bmgd_run_device_buffer(self.h, dev_x, dev_y, rows, compute_stream))

@@ -763,20 +763,18 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
     return trim_records(ctx);
 }
 
-BMGD_API int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const void* next_host_x, const void* next_host_y,
-                                      int64_t next_rows, void* copy_stream, int min_passes, int max_passes, int* passes_done)
+// The adaptive run behind both entry points: passes over the loaded buffer until the buffer that follows has
+// arrived on the device.  That buffer is either given (next_x, next_y, next_rows) or comes from `reader`, which is
+// polled before every pass and whose buffer is copied as soon as it is in host memory.
+static int run_adaptive(bmgd_ctx* ctx, hipStream_t s, hipStream_t cs, const void* next_x, const void* next_y, int64_t next_rows,
+                        bmgd_reader* reader, int min_passes, int max_passes, int* passes_done, int64_t* next_rows_out)
 {
-    if (!ctx) return BMGD_EINVAL;
     if (passes_done) *passes_done = 0;
+    if (next_rows_out) *next_rows_out = 0;
     if (ctx->pending < 0) return fail(ctx, BMGD_ESTATE, "no buffer is loaded");
     if (min_passes < 1 || max_passes < min_passes || max_passes > (1 << 20))
         return fail(ctx, BMGD_EINVAL, "need 1 <= min_passes <= max_passes <= 2^20");
-    const bool have_next = next_host_x != nullptr || next_host_y != nullptr;
-    if (have_next && (!next_host_x || !next_host_y)) return fail(ctx, BMGD_EINVAL, "next_host_x and next_host_y go together");
-    if (have_next && (next_rows < 1 || next_rows > ctx->cfg.buffer_n))
-        return fail(ctx, BMGD_EINVAL, "next_rows must be in [1, buffer_n]");
     HIP_TRY(ctx, hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(compute_stream);
     Slot& slot = ctx->slots[ctx->pending];
     RunRecord rec = ctx->pending_copy;
     ctx->pending_copy = RunRecord();
@@ -789,25 +787,48 @@ BMGD_API int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const
     ctx->used_compute = true;
 
     // the buffering step for the next buffer, into the other slot (Section 2.1: both steps at the same time)
+    enum { kAwaitingHost, kCopying, kNone } next = next_x ? kAwaitingHost : (reader ? kAwaitingHost : kNone);
     RunRecord next_rec;
     int next_slot = -1;
-    if (have_next) {
-        const int rc = enqueue_load(ctx, next_host_x, next_host_y, next_rows, static_cast<hipStream_t>(copy_stream), next_rec,
-                                    &next_slot);
+    auto start_copy = [&](bool block) -> int {
+        const void *x = next_x, *y = next_y;
+        int64_t rows = next_rows;
+        if (reader) {
+            int end = 0;
+            const int rc = reader_take(reader, block, &x, &y, &rows, &end);
+            if (rc != BMGD_OK) return fail(ctx, rc, std::string("reader: ") + bmgd_reader_last_error(reader));
+            if (end) { next = kNone; return BMGD_OK; }
+            if (!x) return BMGD_OK;                      // not in host memory yet
+            if (rows > ctx->cfg.buffer_n) {
+                (void)bmgd_reader_release(reader, nullptr, 0);
+                return fail(ctx, BMGD_EINVAL, "the reader's buffers are larger than buffer_n");
+            }
+        }
+        const int rc = enqueue_load(ctx, x, y, rows, cs, next_rec, &next_slot);
+        if (reader) (void)bmgd_reader_release(reader, cs, rc == BMGD_OK);
         if (rc != BMGD_OK) return rc;
-    }
+        if (next_rows_out) *next_rows_out = rows;
+        next = kCopying;
+        return BMGD_OK;
+    };
 
     // One pass per launch; at most two passes enqueued and unfinished, so that the decision to stop lags the arrival
     // of the next buffer by at most two passes and the device still never runs dry.
     int passes = 0;
     hipEvent_t last = nullptr, in_flight[2] = {nullptr, nullptr};
     for (;;) {
+        if (next == kAwaitingHost) {
+            const int rc = start_copy(false);
+            if (rc != BMGD_OK) return rc;
+        }
         if (passes >= max_passes) break;
         if (passes >= min_passes) {
-            if (!have_next) break;
-            const hipError_t q = hipEventQuery(next_rec.copy_end);
-            if (q == hipSuccess) break;
-            if (q != hipErrorNotReady) return hip_fail(ctx, q, "hipEventQuery(copy of the next buffer)");
+            if (next == kNone) break;
+            if (next == kCopying) {
+                const hipError_t q = hipEventQuery(next_rec.copy_end);
+                if (q == hipSuccess) break;
+                if (q != hipErrorNotReady) return hip_fail(ctx, q, "hipEventQuery(copy of the next buffer)");
+            }
         }
         if (in_flight[0]) HIP_TRY(ctx, hipEventSynchronize(in_flight[0]));
         hipEvent_t chunk = nullptr;
@@ -825,10 +846,37 @@ BMGD_API int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const
     rec.n_chain = (int)(ctx->open_chain.size() - chain0);
     rec.n_prep = (int)(ctx->open_prep.size() - prep0);
     ctx->open_records.push_back(rec);
+    ctx->pending = -1;
+    if (passes_done) *passes_done = passes;
+    // max_passes reached before the reader had the next buffer: wait for it now, so that the call ends as promised
+    if (next == kAwaitingHost) {
+        const int rc = start_copy(true);
+        if (rc != BMGD_OK) return rc;
+    }
     ctx->pending = next_slot;
     ctx->pending_copy = next_rec;
-    if (passes_done) *passes_done = passes;
     return trim_records(ctx);
+}
+
+BMGD_API int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const void* next_host_x, const void* next_host_y,
+                                      int64_t next_rows, void* copy_stream, int min_passes, int max_passes, int* passes_done)
+{
+    if (!ctx) return BMGD_EINVAL;
+    const bool have_next = next_host_x != nullptr || next_host_y != nullptr;
+    if (have_next && (!next_host_x || !next_host_y)) return fail(ctx, BMGD_EINVAL, "next_host_x and next_host_y go together");
+    if (have_next && (next_rows < 1 || next_rows > ctx->cfg.buffer_n))
+        return fail(ctx, BMGD_EINVAL, "next_rows must be in [1, buffer_n]");
+    return run_adaptive(ctx, static_cast<hipStream_t>(compute_stream), static_cast<hipStream_t>(copy_stream), next_host_x,
+                        next_host_y, next_rows, nullptr, min_passes, max_passes, passes_done, nullptr);
+}
+
+BMGD_API int bmgd_run_buffer_adaptive_reader(bmgd_ctx* ctx, void* compute_stream, bmgd_reader* reader, void* copy_stream,
+                                             int min_passes, int max_passes, int* passes_done, int64_t* next_rows)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!reader) return fail(ctx, BMGD_EINVAL, "reader must not be NULL");
+    return run_adaptive(ctx, static_cast<hipStream_t>(compute_stream), static_cast<hipStream_t>(copy_stream), nullptr, nullptr,
+                        0, reader, min_passes, max_passes, passes_done, next_rows);
 }
 
 BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* compute_stream)

@@ -5,6 +5,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+struct bmgd_reader;
+// Reader (reader.hip): hand out the next buffer if it is in host memory (*x = NULL if not; block = wait for it);
+// *end = 1 once the data set has been delivered completely.  Status code as the public calls.
+int reader_take(bmgd_reader* r, bool block, const void** x, const void** y, int64_t* rows, int* end);
+
 namespace bmgd {
 
 constexpr int kPermRounds = 8;
