@@ -22,7 +22,7 @@
  * bmgd_run_buffer().  All work is enqueued on the caller's HIP streams (plus,
  * in BMGD_CHAIN_GRAM mode, one stream of the library's own, see below); the
  * calls that block the host are bmgd_get_theta(), bmgd_set_theta(),
- * bmgd_get_perm(), bmgd_get_stats(), bmgd_sync(), bmgd_eval_loss(),
+ * bmgd_get_perm(), bmgd_get_stats(), bmgd_sync(), bmgd_eval_loss(), bmgd_get_swa(),
  * bmgd_set_lr_schedule(), bmgd_reset_optimizer(), bmgd_destroy() and (for
  * part of its passes) bmgd_run_buffer_adaptive().
  * The run calls keep a few events per buffer for the statistics; once 4096
@@ -219,6 +219,28 @@ int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream);
 int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const void* next_host_x, const void* next_host_y,
                              int64_t next_rows, void* copy_stream, int min_passes, int max_passes, int* passes_done);
 
+/* ---- Running on part of a buffer (Section 4.2: for data with few positive responses the negative instances of
+ * each buffer are undersampled, so that mini-batches are roughly balanced) ---------------------------------------
+ * The next run call (any of them; one run only) works on the rows dev_idx[0 .. count) of its buffer instead of all
+ * of them: it partitions those count rows, M = ceil(count / batch_n), PERM(seed, b, t, count), and a row may be
+ * listed more than once.  Which rows to keep is the caller's choice (e.g. all positives and as many negatives drawn
+ * at random).  dev_idx: device memory, int32, valid until the run has completed; count <= rows of the buffer
+ * (checked when the run is enqueued); count = 0 cancels.  Entries outside the buffer are not followed: row 0 is used
+ * in their place and the next blocking call returns BMGD_EINVAL. */
+int bmgd_set_row_subset(bmgd_ctx* ctx, const int32_t* dev_idx, int64_t count);
+
+/* ---- Averaging of estimates (Section 4.4: the buffering idea combined with stochastic weight averaging, which
+ * averages the weights after every so many epochs) --------------------------------------------------------------
+ * bmgd_swa_update folds the estimate as it stands after all runs enqueued so far into a running average kept on
+ * the device: avg <- avg + (theta - avg) / k for the k-th call (the first call copies theta).  The caller decides
+ * when (say after every five buffers).  Asynchronous: one small kernel, enqueued behind the last update of theta;
+ * compute_stream must be the stream of the run calls.  bmgd_get_swa copies the average to host_out (layout and len
+ * as bmgd_get_theta; blocks) and stores the number of snapshots in *count (may be NULL); BMGD_ESTATE before the
+ * first update.  bmgd_swa_reset makes the next update start a new average. */
+int bmgd_swa_update(bmgd_ctx* ctx, void* compute_stream);
+int bmgd_get_swa(bmgd_ctx* ctx, float* host_out, int64_t len, int64_t* count);
+int bmgd_swa_reset(bmgd_ctx* ctx);
+
 /* ---- Reading buffers from storage (the first of the two transfers of Section 2.1) -----------------------------
  * A reader owns a host thread that reads consecutive buffers of a data set from two flat files into a ring of
  * pinned host buffers, ahead of the consumer, so that bmgd_load_buffer_async() always finds its next buffer in
@@ -285,7 +307,7 @@ int bmgd_reset_optimizer(bmgd_ctx* ctx);
 int bmgd_set_lr(bmgd_ctx* ctx, double lr);
 int bmgd_set_passes(bmgd_ctx* ctx, int passes);
 
-/* A learning rate per mini-batch update (Theorem 4 lets alpha vary over the run; Section 4.3 trains with a cosine
+/* A learning rate per mini-batch update (Theorem 4 lets alpha vary over the run; Section 4.4 trains with a cosine
  * schedule): the u-th update enqueued after this call (u = 0, 1, ...) uses host_alphas[min(u, len - 1)], whatever
  * buffer and pass it belongs to; lr and bmgd_set_lr are ignored while a schedule is set.  len = 0 (host_alphas may
  * then be NULL) removes the schedule.  Every value must be finite and > 0.  The table is copied: to device memory

@@ -102,7 +102,7 @@ class BMGD:
         self.theta = np.zeros(shape) if theta0 is None else np.array(theta0, dtype=np.float64).reshape(shape)
         self.b = 0
         self.steps = 0
-        # Optional learning rate per mini-batch update (Theorem 4 lets alpha change over the run; Section 4.3 uses
+        # Optional learning rate per mini-batch update (Theorem 4 lets alpha change over the run; Section 4.4 uses
         # a cosine schedule): update number u, counted from the moment the schedule is set, uses
         # lr_schedule[min(u, len - 1)]; None = the constant self.alpha.
         self.lr_schedule = None
@@ -148,6 +148,15 @@ class BMGD:
             self.theta = self.theta - a * mhat / (np.sqrt(shat) + self.eps)
         else:
             raise ValueError("unknown optimizer")
+
+    def swa_update(self) -> None:
+        """Fold the current estimate into the running average of estimates (Section 4.4, weight averaging every so
+        many buffer epochs): after k calls self.swa is the plain mean of the k estimates."""
+        self.swa_count = getattr(self, "swa_count", 0) + 1
+        if self.swa_count == 1:
+            self.swa = self.theta.copy()
+        else:
+            self.swa = self.swa + (self.theta - self.swa) / self.swa_count
 
     def step_size(self) -> float:
         """Learning rate of the update about to be made."""

@@ -26,6 +26,7 @@ BMGD_OPT_SGD, BMGD_OPT_MOMENTUM, BMGD_OPT_NAG, BMGD_OPT_ADAM = 0, 1, 2, 3
 
 EXPORTS = [
     "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
+    "bmgd_set_row_subset", "bmgd_swa_update", "bmgd_get_swa", "bmgd_swa_reset",
     "bmgd_reader_open", "bmgd_reader_acquire", "bmgd_reader_release", "bmgd_load_from_reader", "bmgd_run_buffer_adaptive_reader", "bmgd_reader_stats",
     "bmgd_reader_last_error", "bmgd_reader_close",
     "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_buffer_adaptive", "bmgd_run_device_buffer", "bmgd_get_theta",
@@ -74,6 +75,10 @@ def _load() -> C.CDLL:
     lib.bmgd_run_device_buffer.argtypes, lib.bmgd_run_device_buffer.restype = [vp, vp, vp, i64, vp], i32
     lib.bmgd_run_buffer_adaptive.argtypes = [vp, vp, vp, vp, i64, vp, C.c_int, C.c_int, C.POINTER(C.c_int)]
     lib.bmgd_run_buffer_adaptive.restype = i32
+    lib.bmgd_set_row_subset.argtypes, lib.bmgd_set_row_subset.restype = [vp, vp, i64], i32
+    lib.bmgd_swa_update.argtypes, lib.bmgd_swa_update.restype = [vp, vp], i32
+    lib.bmgd_get_swa.argtypes, lib.bmgd_get_swa.restype = [vp, vp, i64, C.POINTER(i64)], i32
+    lib.bmgd_swa_reset.argtypes, lib.bmgd_swa_reset.restype = [vp], i32
     lib.bmgd_reader_open.argtypes = [C.c_char_p, C.c_char_p, i64, i32, i64, i64, i32, i32, C.POINTER(vp)]
     lib.bmgd_reader_open.restype = i32
     lib.bmgd_reader_acquire.argtypes, lib.bmgd_reader_acquire.restype = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(i64)], i32
@@ -234,6 +239,24 @@ class BmgdError(RuntimeError):
         self.code = code
 
 
+def bmgd_set_row_subset(ctx, dev_idx, count) -> int:
+    return lib.bmgd_set_row_subset(ctx, _ptr(dev_idx), count)
+
+
+def bmgd_swa_update(ctx, compute_stream=None) -> int:
+    return lib.bmgd_swa_update(ctx, _stream(compute_stream))
+
+
+def bmgd_get_swa(ctx, host_out, length):
+    count = C.c_int64(0)
+    rc = lib.bmgd_get_swa(ctx, _ptr(host_out), length, C.byref(count))
+    return rc, count.value
+
+
+def bmgd_swa_reset(ctx) -> int:
+    return lib.bmgd_swa_reset(ctx)
+
+
 def bmgd_reader_open(x_path, y_path, p, x_dtype, n_rows, buffer_n, ring_slots, loop):
     h = C.c_void_p()
     rc = lib.bmgd_reader_open(os.fsencode(x_path), os.fsencode(y_path), p, x_dtype, n_rows, buffer_n, ring_slots,
@@ -371,6 +394,25 @@ class Context:
                                             min_passes, max_passes)
         self._check(rc)
         return done
+
+    def set_row_subset(self, dev_idx, count):
+        """Restrict the next run to rows dev_idx[:count] (an int32 device tensor) of its buffer."""
+        self._check(bmgd_set_row_subset(self.h, dev_idx, count))
+
+    def swa_update(self, compute_stream=None):
+        self._check(bmgd_swa_update(self.h, compute_stream))
+
+    def get_swa(self):
+        """(running average of the estimates folded in by swa_update, number of them)."""
+        out = np.empty(self.theta_len, dtype=np.float32)
+        rc, count = bmgd_get_swa(self.h, out, self.theta_len)
+        self._check(rc)
+        if self.cfg.model == BMGD_SOFTMAX:
+            out = out.reshape(self.cfg.p, self.cfg.n_classes)
+        return out, count
+
+    def swa_reset(self):
+        self._check(bmgd_swa_reset(self.h))
 
     def run_buffer_adaptive_reader(self, compute_stream, reader, copy_stream, min_passes, max_passes):
         """Like run_buffer_adaptive with the next buffer taken from `reader`; returns (passes made, rows of the buffer now

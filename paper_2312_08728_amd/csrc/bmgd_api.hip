@@ -25,7 +25,7 @@ constexpr int kMaxGroups = 256;                    // upper bound used to size t
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, opt_m, opt_s, opt_len, eval, total;
+    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, opt_m, opt_s, opt_len, eval, swa, total;
 };
 
 struct Slot {
@@ -88,6 +88,11 @@ struct bmgd_ctx {
     std::vector<float> lr_tab_host;
     int64_t lr_pos = 0;
     // optimizer state (kind != BMGD_OPT_SGD): arrays laid out like theta, update count for Adam's bias corrections
+    const int32_t* subset = nullptr;               // rows the next run is restricted to (device; bmgd_set_row_subset)
+    int64_t subset_count = 0;
+    int64_t subset_limit = 0;                      // rows of the buffer those indices refer to (set when the run starts)
+    float* swa = nullptr;                          // running average of theta, swa_count snapshots so far
+    int64_t swa_count = 0;
     float* opt_m = nullptr;
     float* opt_s = nullptr;
     int64_t opt_k = 0;
@@ -214,6 +219,8 @@ Layout make_layout(const bmgd_config& c)
         if (c.optimizer == BMGD_OPT_ADAM) off += align_up(l.opt_len * 4);
     }
     l.eval = off; off += align_up((size_t)kEvalBlocks * sizeof(double));   // partial sums of bmgd_eval_loss
+    // running average of the estimate (bmgd_swa_update), laid out like theta
+    l.swa = off; off += align_up(c.model == BMGD_SOFTMAX ? (size_t)c.p * softmax_dims(c.p, c.batch_n, C).c_pad * 4 : (size_t)c.p * 4);
     l.total = off;
     return l;
 }
@@ -331,11 +338,13 @@ int drain(bmgd_ctx* ctx)
     if (ctx->chain_stream) HIP_TRY(ctx, hipStreamSynchronize(ctx->chain_stream));
     ctx->chain_pending[0] = ctx->chain_pending[1] = false;
     settle_records(ctx, ctx->open_records.size());
-    unsigned flag = 0;
-    HIP_TRY(ctx, hipMemcpy(&flag, ctx->sync + 1, sizeof flag, hipMemcpyDeviceToHost));
-    if (flag != 0) {
+    unsigned flag[2] = {0, 0};
+    HIP_TRY(ctx, hipMemcpy(flag, ctx->sync + 1, sizeof flag, hipMemcpyDeviceToHost));
+    if (flag[0] != 0 || flag[1] != 0) {
         HIP_TRY(ctx, hipMemset(ctx->sync, 0, 64));
-        return fail(ctx, BMGD_EHIP, "a device-side wait exceeded barrier_timeout_us; the run was abandoned and theta is not valid");
+        if (flag[0] != 0)
+            return fail(ctx, BMGD_EHIP, "a device-side wait exceeded barrier_timeout_us; the run was abandoned and theta is not valid");
+        return fail(ctx, BMGD_EINVAL, "a row subset held an index outside its buffer (row 0 was used in its place); theta is not valid");
     }
     return BMGD_OK;
 }
@@ -396,7 +405,7 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
             ctx->open_prep.emplace_back(pv0, pv1);
             // set i is free once the chain that read it last has finished
             if (ctx->chain_pending[i]) HIP_TRY(ctx, hipStreamWaitEvent(stream, ctx->chain_done[i], 0));
-            HIP_TRY(ctx, launch_perm(ctx->gram_perm[i], rows, nperm, keys, stream));
+            HIP_TRY(ctx, launch_perm(ctx->gram_perm[i], rows, nperm, keys, stream, ctx->subset, ctx->subset_limit, ctx->sync + 2));
             HIP_TRY(ctx, gram_launch_moments(static_cast<const float*>(x), static_cast<const float*>(y), ctx->gram_perm[i],
                                              ctx->gram[i], (int)rows, (int)c.p, (int)n, np, fixed ? 0 : (int)rows, stream,
                                              pv0, pv1));
@@ -416,7 +425,8 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
             if (chunk_end) *chunk_end = ev1;
             continue;
         }
-        if (!fixed || t0 == 0) HIP_TRY(ctx, launch_perm(ctx->perm, rows, nperm, keys, stream));
+        if (!fixed || t0 == 0)
+            HIP_TRY(ctx, launch_perm(ctx->perm, rows, nperm, keys, stream, ctx->subset, ctx->subset_limit, ctx->sync + 2));
         if (c.model == BMGD_SOFTMAX) {
             HIP_TRY(ctx, hipEventRecord(ev0, stream));
             const SoftmaxDims d = softmax_dims(c.p, n, c.n_classes);
@@ -517,6 +527,19 @@ void finish_run(bmgd_ctx* ctx, int64_t rows, int64_t passes)
     ctx->steps += passes * batches_of(rows, n);
     ctx->sample_gradients += passes * rows;
     ctx->buffer_counter += 1;
+}
+
+// Rows the run over a buffer of `buffer_rows` rows works on: all of them, or the subset set for this run.
+// Returns 0 (with the error set) if the subset does not fit the buffer.
+int64_t rows_of_run(bmgd_ctx* ctx, int64_t buffer_rows)
+{
+    if (!ctx->subset) return buffer_rows;
+    if (ctx->subset_count > buffer_rows) {
+        fail(ctx, BMGD_EINVAL, "the row subset has more entries than the buffer has rows");
+        return 0;
+    }
+    ctx->subset_limit = buffer_rows;
+    return ctx->subset_count;
 }
 
 // Enqueue the T passes of Algorithm 1 over (x, y, rows).
@@ -643,6 +666,7 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->gram[1] = reinterpret_cast<float*>(base + ctx->lay.gram[1]);
     ctx->gram_perm[0] = ctx->perm;
     ctx->gram_perm[1] = reinterpret_cast<int32_t*>(base + ctx->lay.gram_perm);
+    ctx->swa = reinterpret_cast<float*>(base + ctx->lay.swa);
     ctx->opt_m = reinterpret_cast<float*>(base + ctx->lay.opt_m);
     ctx->opt_s = reinterpret_cast<float*>(base + ctx->lay.opt_s);
     if (ctx->lay.total > ctx->lay.opt_m) CREATE_TRY(hipMemset(ctx->opt_m, 0, ctx->lay.total - ctx->lay.opt_m));
@@ -740,6 +764,8 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t s = static_cast<hipStream_t>(compute_stream);
     Slot& slot = ctx->slots[ctx->pending];
+    const int64_t run_rows = rows_of_run(ctx, slot.rows);
+    if (run_rows == 0) return BMGD_EINVAL;
     RunRecord rec = ctx->pending_copy;
     rec.start = take_event(ctx); rec.end = take_event(ctx);
     if (!rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
@@ -747,7 +773,8 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
     HIP_TRY(ctx, hipEventRecord(rec.start, s));
     hipEvent_t last = nullptr;
     const size_t chain0 = ctx->open_chain.size(), prep0 = ctx->open_prep.size();
-    const int rc = enqueue_compute(ctx, slot.x, slot.y, slot.rows, s, &last);
+    const int rc = enqueue_compute(ctx, slot.x, slot.y, run_rows, s, &last);
+    ctx->subset = nullptr;                                        // a subset holds for one run
     ctx->last_compute = s;
     ctx->used_compute = true;
     if (rc != BMGD_OK) return rc;
@@ -776,6 +803,8 @@ static int run_adaptive(bmgd_ctx* ctx, hipStream_t s, hipStream_t cs, const void
         return fail(ctx, BMGD_EINVAL, "need 1 <= min_passes <= max_passes <= 2^20");
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     Slot& slot = ctx->slots[ctx->pending];
+    const int64_t run_rows = rows_of_run(ctx, slot.rows);
+    if (run_rows == 0) return BMGD_EINVAL;
     RunRecord rec = ctx->pending_copy;
     ctx->pending_copy = RunRecord();
     rec.start = take_event(ctx); rec.end = take_event(ctx);
@@ -832,13 +861,14 @@ static int run_adaptive(bmgd_ctx* ctx, hipStream_t s, hipStream_t cs, const void
         }
         if (in_flight[0]) HIP_TRY(ctx, hipEventSynchronize(in_flight[0]));
         hipEvent_t chunk = nullptr;
-        const int rc = enqueue_passes(ctx, slot.x, slot.y, slot.rows, s, passes, 1, &last, &chunk);
+        const int rc = enqueue_passes(ctx, slot.x, slot.y, run_rows, s, passes, 1, &last, &chunk);
         if (rc != BMGD_OK) return rc;
         in_flight[0] = in_flight[1];
         in_flight[1] = chunk;
         passes += 1;
     }
-    finish_run(ctx, slot.rows, passes);
+    finish_run(ctx, run_rows, passes);
+    ctx->subset = nullptr;
     if (last) { give_event(ctx, rec.end); rec.end = last; rec.owns_end = false; }
     else HIP_TRY(ctx, hipEventRecord(rec.end, s));
     HIP_TRY(ctx, hipEventRecord(slot.compute_done, s));
@@ -889,13 +919,16 @@ BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void
         return fail(ctx, BMGD_EINVAL, "device buffers must be at least 16-byte aligned");
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t s = static_cast<hipStream_t>(compute_stream);
+    const int64_t run_rows = rows_of_run(ctx, rows);
+    if (run_rows == 0) return BMGD_EINVAL;
     RunRecord rec;
     rec.start = take_event(ctx); rec.end = take_event(ctx);
     if (!rec.start || !rec.end) return fail(ctx, BMGD_EHIP, "could not create events");
     HIP_TRY(ctx, hipEventRecord(rec.start, s));
     hipEvent_t last = nullptr;
     const size_t chain0 = ctx->open_chain.size(), prep0 = ctx->open_prep.size();
-    const int rc = enqueue_compute(ctx, dev_x, dev_y, rows, s, &last);
+    const int rc = enqueue_compute(ctx, dev_x, dev_y, run_rows, s, &last);
+    ctx->subset = nullptr;
     ctx->last_compute = s;
     ctx->used_compute = true;
     if (rc != BMGD_OK) return rc;
@@ -1001,8 +1034,61 @@ BMGD_API int bmgd_reset_optimizer(bmgd_ctx* ctx)
     if (!ctx) return BMGD_EINVAL;
     const int rc = drain(ctx);
     if (rc != BMGD_OK) return rc;
-    if (ctx->lay.total > ctx->lay.opt_m) HIP_TRY(ctx, hipMemset(ctx->opt_m, 0, ctx->lay.total - ctx->lay.opt_m));
+    if (ctx->lay.eval > ctx->lay.opt_m) HIP_TRY(ctx, hipMemset(ctx->opt_m, 0, ctx->lay.eval - ctx->lay.opt_m));
     ctx->opt_k = 0;
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_set_row_subset(bmgd_ctx* ctx, const int32_t* dev_idx, int64_t count)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!dev_idx && count != 0) return fail(ctx, BMGD_EINVAL, "dev_idx must not be NULL unless count is 0");
+    if (count < 0 || count > ctx->cfg.buffer_n) return fail(ctx, BMGD_EINVAL, "count must be in [0, buffer_n]");
+    if ((reinterpret_cast<uintptr_t>(dev_idx) % 4) != 0) return fail(ctx, BMGD_EINVAL, "dev_idx must be 4-byte aligned");
+    ctx->subset = count > 0 ? dev_idx : nullptr;
+    ctx->subset_count = count;
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_swa_update(bmgd_ctx* ctx, void* compute_stream)
+{
+    if (!ctx) return BMGD_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    // behind the last update of theta: in the moment form those run on the library's stream
+    hipStream_t s = ctx->chain == BMGD_CHAIN_GRAM ? ctx->chain_stream : static_cast<hipStream_t>(compute_stream);
+    const size_t n = (ctx->lay.total - ctx->lay.swa) / 4;           // whole array, padding included (stays 0)
+    HIP_TRY(ctx, launch_running_mean(ctx->swa, ctx->theta, n, 1.0f / (float)(ctx->swa_count + 1), ctx->swa_count == 0, s));
+    ctx->swa_count += 1;
+    if (ctx->chain != BMGD_CHAIN_GRAM) {
+        ctx->last_compute = s;
+        ctx->used_compute = true;
+    }
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_get_swa(bmgd_ctx* ctx, float* host_out, int64_t len, int64_t* count)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (count) *count = ctx->swa_count;
+    if (!host_out) return fail(ctx, BMGD_EINVAL, "host_out must not be NULL");
+    if (len != ctx->theta_len) return fail(ctx, BMGD_EINVAL, "len must equal p (p * n_classes for softmax)");
+    if (ctx->swa_count == 0) return fail(ctx, BMGD_ESTATE, "no estimate has been averaged yet");
+    const int rc = drain(ctx);
+    if (rc != BMGD_OK) return rc;
+    if (ctx->cfg.model == BMGD_SOFTMAX) {
+        const SoftmaxDims d = softmax_dims(ctx->cfg.p, ctx->cfg.batch_n, ctx->cfg.n_classes);
+        const size_t C = (size_t)ctx->cfg.n_classes;
+        HIP_TRY(ctx, hipMemcpy2D(host_out, C * 4, ctx->swa, (size_t)d.c_pad * 4, C * 4, (size_t)ctx->cfg.p, hipMemcpyDeviceToHost));
+        return BMGD_OK;
+    }
+    HIP_TRY(ctx, hipMemcpy(host_out, ctx->swa, (size_t)len * 4, hipMemcpyDeviceToHost));
+    return BMGD_OK;
+}
+
+BMGD_API int bmgd_swa_reset(bmgd_ctx* ctx)
+{
+    if (!ctx) return BMGD_EINVAL;
+    ctx->swa_count = 0;                                  // the next bmgd_swa_update starts over from its snapshot
     return BMGD_OK;
 }
 

@@ -27,10 +27,17 @@ void perm_round_keys(uint64_t seed, uint32_t b, uint32_t t, uint32_t out[kPermRo
 int perm_half_width(int64_t rows);
 
 // Device: out[pass][j] = PERM(...)[j] for j < rows, pass < npass (row stride = rows).
-hipError_t launch_perm(int32_t* out, int64_t rows, int npass, const PermKeys& keys, hipStream_t stream);
+// subset != NULL: out[pass][j] = subset[PERM(...)[j]] (a partition of the rows subset[0 .. rows) of a buffer of `limit`
+// rows); an entry outside [0, limit) is replaced by 0 and *bad is set to 1.
+hipError_t launch_perm(int32_t* out, int64_t rows, int npass, const PermKeys& keys, hipStream_t stream,
+                       const int32_t* subset = nullptr, int64_t limit = 0, unsigned* bad = nullptr);
 
 // Device: zero `bytes` bytes at dst (both multiples of 16) with a kernel, in stream order.
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t stream);
+
+// Device: running mean of snapshots of theta (n floats), in stream order: avg <- theta if `first`, else
+// avg <- avg + (theta - avg) * inv.
+hipError_t launch_running_mean(float* avg, const float* theta, size_t n, float inv, bool first, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------------
 // Update rules fed with the mini-batch gradient (Section 4.3: buffered NAG and Adam).

@@ -40,8 +40,11 @@ __device__ inline uint32_t feistel(uint32_t x, const KeyRow& key, uint32_t h, ui
     return (left << h) | right;
 }
 
+// With `subset` the partition is one of the rows subset[0 .. rows) of a larger buffer: out holds subset[PERM[j]].
+// An entry outside [0, limit) is replaced by row 0 and reported through *bad (the host turns that into an error).
 __global__ void __launch_bounds__(256) perm_kernel(int32_t* __restrict__ out, uint32_t rows, uint32_t h,
-                                                   PermKeys keys)
+                                                   PermKeys keys, const int32_t* __restrict__ subset, uint32_t limit,
+                                                   unsigned* bad)
 {
     const uint32_t pass = blockIdx.y;
     const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -53,6 +56,11 @@ __global__ void __launch_bounds__(256) perm_kernel(int32_t* __restrict__ out, ui
     // j < rows lies on a cycle of the bijection that returns to j, so the walk always re-enters [0, rows).
     uint32_t x = feistel(j, key, h, mask);
     while (x >= rows) x = feistel(x, key, h, mask);
+    if (subset) {
+        const uint32_t v = (uint32_t)subset[x];
+        if (v >= limit) __hip_atomic_store(bad, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        x = v < limit ? v : 0u;
+    }
     out[(size_t)pass * rows + j] = (int32_t)x;
 }
 
@@ -62,7 +70,26 @@ __global__ void __launch_bounds__(256) fill_zero_kernel(uint4* __restrict__ dst,
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
 }
 
+// avg <- theta for the first snapshot, else avg + (theta - avg) * inv with inv = 1 / (snapshots so far + 1)
+__global__ void __launch_bounds__(256) running_mean_kernel(float* __restrict__ avg, const float* __restrict__ theta, size_t n,
+                                                           float inv, int first)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const float t = theta[i];
+        avg[i] = first ? t : avg[i] + (t - avg[i]) * inv;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_running_mean(float* avg, const float* theta, size_t n, float inv, bool first, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, 2048);
+    hipLaunchKernelGGL(running_mean_kernel, dim3(blocks), dim3(256), 0, stream, avg, theta, n, inv, first ? 1 : 0);
+    return hipGetLastError();
+}
 
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t stream)
 {
@@ -91,13 +118,15 @@ int perm_half_width(int64_t rows)
     return h < 1 ? 1 : h;
 }
 
-hipError_t launch_perm(int32_t* out, int64_t rows, int npass, const PermKeys& keys, hipStream_t stream)
+hipError_t launch_perm(int32_t* out, int64_t rows, int npass, const PermKeys& keys, hipStream_t stream, const int32_t* subset,
+                       int64_t limit, unsigned* bad)
 {
     if (rows <= 0 || npass <= 0) return hipSuccess;
     if (npass > kMaxPassesPerLaunch || rows > (int64_t(1) << 30)) return hipErrorInvalidValue;
+    if (subset && (!bad || limit < rows || limit > (int64_t(1) << 30))) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((rows + 255) / 256), (unsigned)npass);
     hipLaunchKernelGGL(perm_kernel, grid, dim3(256), 0, stream, out, (uint32_t)rows,
-                       (uint32_t)perm_half_width(rows), keys);
+                       (uint32_t)perm_half_width(rows), keys, subset, (uint32_t)limit, bad);
     return hipGetLastError();
 }
 

@@ -201,7 +201,7 @@ def test_schedules_of_learning_rate_and_passes():
 @pytest.mark.parametrize("model,p,n,chain", [(wl.LOGISTIC, 40, 250, 1), (wl.LOGISTIC, 200, 512, 1), (wl.LINEAR, 1024, 500, 1),
                                              (wl.LINEAR, 2304, 600, 1), (wl.LINEAR, 40, 250, 3), (wl.LINEAR, 100, 300, 3), (wl.LOGISTIC, 40, 250, 2)])
 def test_learning_rate_per_update(model, p, n, chain):
-    """A cosine table of learning rates over the updates of the whole run (Section 4.3), shorter than the run so that
+    """A cosine table of learning rates over the updates of the whole run (Section 4.4), shorter than the run so that
     its last value has to persist, crossing passes, launches (T = 5 > 4 passes per launch) and buffers; then cleared."""
     import torch
     import paper_2312_08728_amd as B

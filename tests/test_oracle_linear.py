@@ -193,7 +193,7 @@ def test_ragged_last_batch_is_averaged_over_its_own_size():
 
 
 def test_per_update_learning_rates_hand_unrolled_and_special_cases():
-    """A learning rate per mini-batch update (Theorem 4; cosine schedule of Section 4.3): written out with scalars on
+    """A learning rate per mini-batch update (Theorem 4; cosine schedule of Section 4.4): written out with scalars on
     N0 = 4, p = 1, n = 2 over two buffers; the table's last value persists; a constant table is the constant rate;
     and with full batches and rates 1/lambda on an orthogonal design one update lands on the OLS solution."""
     x = [1.0, -2.0, 0.5, 3.0]

@@ -130,3 +130,22 @@ def test_state_is_carried_across_buffers_and_passes():
                     idx = pm[s0:s0 + 50]
                     ref.apply(Xb[idx].T @ (Xb[idx] @ ref.theta - yb[idx]) / 50)
         assert np.allclose(st.theta, ref.theta, rtol=0, atol=1e-13)
+
+
+def test_running_average_of_estimates_is_their_plain_mean():
+    """Weight averaging (Section 4.4): after k snapshots the running average equals the arithmetic mean of the k
+    estimates, whatever happened between them; a single snapshot is the estimate itself."""
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((600, 6))
+    y = X @ rng.standard_normal(6) + 0.1 * rng.standard_normal(600)
+    st = bmgd.BMGD(bmgd.LINEAR, 6, 50, 0.05, 2)
+    snaps = []
+    for k in range(6):
+        st.run_buffer(X[k * 100:(k + 1) * 100], y[k * 100:(k + 1) * 100])
+        if k % 2 == 1:
+            st.swa_update()
+            snaps.append(st.theta.copy())
+            np.testing.assert_allclose(st.swa, np.mean(snaps, axis=0), rtol=0, atol=1e-15)
+    assert st.swa_count == 3
+    assert np.array_equal(snaps[0], np.mean(snaps[:1], axis=0))
+    assert not np.allclose(st.swa, st.theta)
