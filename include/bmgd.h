@@ -181,7 +181,8 @@ bmgd_ctx* bmgd_create(int64_t p, int64_t buffer_n, int64_t batch_n, double lr, i
  * reaches 2^23 (step indices inside one kernel launch are kept below that). */
 int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out);
 
-/* Device bytes a context with this configuration needs (two buffer slots, partitions, theta, scratch; in
+/* Device bytes a context with this configuration needs (two buffer slots, partitions, theta and its running
+ * average, optimizer state, scratch; in
  * BMGD_CHAIN_GRAM mode also 4 * ceil(buffer_n / batch_n) * (p + 1) * roundup(p, 4) floats of moment matrices);
  * 0 if the configuration is invalid.  Needs no GPU. */
 size_t bmgd_workspace_bytes(const bmgd_config* cfg);

@@ -141,6 +141,32 @@ __device__ __forceinline__ void ll_load4(const unsigned long long* const (&src)[
                  : "memory");
 }
 
+// The same with eight words per trip (wide rows: a thread has eight words to fetch per exchange, and two trips of four
+// cost twice the latency of the fabric).
+__device__ __forceinline__ void ll_load8(const unsigned long long* const (&src)[8], unsigned long long (&w)[8])
+{
+    asm volatile("global_load_dwordx2 %0, %8, off sc1\n\t"
+                 "global_load_dwordx2 %1, %9, off sc1\n\t"
+                 "global_load_dwordx2 %2, %10, off sc1\n\t"
+                 "global_load_dwordx2 %3, %11, off sc1\n\t"
+                 "global_load_dwordx2 %4, %12, off sc1\n\t"
+                 "global_load_dwordx2 %5, %13, off sc1\n\t"
+                 "global_load_dwordx2 %6, %14, off sc1\n\t"
+                 "global_load_dwordx2 %7, %15, off sc1\n\t"
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]), "=&v"(w[3]), "=&v"(w[4]), "=&v"(w[5]), "=&v"(w[6]), "=&v"(w[7])
+                 : "v"(src[0]), "v"(src[1]), "v"(src[2]), "v"(src[3]), "v"(src[4]), "v"(src[5]), "v"(src[6]), "v"(src[7])
+                 : "memory");
+}
+
+template <int U>
+__device__ __forceinline__ void ll_load_n(const unsigned long long* const (&src)[U], unsigned long long (&w)[U])
+{
+    static_assert(U == 4 || U == 8, "four or eight words per trip");
+    if constexpr (U == 4) ll_load4(src, w);
+    else ll_load8(src, w);
+}
+
 // Every wait is bounded: a poll that has failed for `timeout` ticks of the 100 MHz wall clock raises the
 // abort flag, which every other poller checks, and the kernel exits.
 struct PollGuard {
@@ -179,11 +205,10 @@ struct ExchangeCtx {
 // `apply(c, sum)` runs once per column.  Leaves *s_abort set if a wait ran out.
 // Thread (gs, cj) fetches column c_lo + cj of workgroups gs, gs + NG, ...: four words are requested back to
 // back and awaited together, so a thread pays one trip over the fabric per four workgroups.
-template <class F>
+template <int U = 4, class F>
 __device__ __forceinline__ void gather_columns_impl(const ExchangeCtx& x, const unsigned long long* words, int c_lo,
                                                     int c_hi, unsigned tag, F&& apply)
 {
-    constexpr int U = 4;
     const int width = c_hi - c_lo;
     if (width <= 0) return;
     const int W = min(width, x.block);
@@ -201,7 +226,7 @@ __device__ __forceinline__ void gather_columns_impl(const ExchangeCtx& x, const 
                 for (int u = 0; u < U; ++u) src[u] = words + (size_t)min(g0 + u * NG, x.G - 1) * x.pp + c;
                 unsigned long long w[U];
                 for (;;) {
-                    ll_load4(src, w);
+                    ll_load_n<U>(src, w);
                     bool ready = true;
 #pragma unroll
                     for (int u = 0; u < U; ++u)
@@ -238,14 +263,14 @@ __device__ __forceinline__ void gather_columns_impl(const ExchangeCtx& x, const 
 // new values in kThetaCopies copies (a workgroup polls copy (its index mod kThetaCopies), so no single set
 // of words is polled by the whole grid); then everyone collects the whole updated theta into th_lds.
 // Returns true when a wait ran out.
-template <class F>
+template <int U = 4, class F>
 __device__ __forceinline__ bool sliced_update(const ExchangeCtx& x, const unsigned long long* words,
                                               unsigned long long* thw, float* th_lds, unsigned tag, F&& new_theta)
 {
     const int cw = ((x.p + x.G - 1) / x.G + 15) & ~15;   // slices are whole lines of 16 words
     const int c_lo = min(x.p, (int)blockIdx.x * cw), c_hi = min(x.p, c_lo + cw);
     const int pp = x.pp;
-    gather_columns_impl(x, words, c_lo, c_hi, tag, [&](int c, float t) {
+    gather_columns_impl<U>(x, words, c_lo, c_hi, tag, [&](int c, float t) {
         const float v = new_theta(c, t);
 #pragma unroll
         for (int r = 0; r < kThetaCopies; ++r) ll_store(thw + (size_t)r * pp + c, v, tag);
@@ -254,22 +279,22 @@ __device__ __forceinline__ bool sliced_update(const ExchangeCtx& x, const unsign
     if (*x.s_abort) return true;
     const unsigned long long* mine = thw + (size_t)(blockIdx.x % kThetaCopies) * pp;
     bool dead = false;
-    for (int c0 = x.tid; c0 < x.p && !dead; c0 += 4 * x.block) {   // four words per trip over the fabric
-        const unsigned long long* src[4];
+    for (int c0 = x.tid; c0 < x.p && !dead; c0 += U * x.block) {   // U words per trip over the fabric
+        const unsigned long long* src[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) src[u] = mine + min(c0 + u * x.block, x.p - 1);
-        unsigned long long w[4];
+        for (int u = 0; u < U; ++u) src[u] = mine + min(c0 + u * x.block, x.p - 1);
+        unsigned long long w[U];
         for (;;) {
-            ll_load4(src, w);
+            ll_load_n<U>(src, w);
             bool ready = true;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) ready = ready && (unsigned)(w[u] >> 32) == tag;
+            for (int u = 0; u < U; ++u) ready = ready && (unsigned)(w[u] >> 32) == tag;
             if (ready) break;
             if (x.guard->expired()) { dead = true; break; }
         }
         if (dead) break;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < U; ++u)
             if (c0 + u * x.block < x.p) th_lds[c0 + u * x.block] = __builtin_bit_cast(float, (unsigned)w[u]);
     }
     if (dead) *x.s_abort = 1;
@@ -748,11 +773,11 @@ __global__ void __launch_bounds__(kWideBlock) glm_wide_kernel(GlmArgs a)
             return v;
         };
         if (a.reduce_mode == kReduceRedundant) {
-            gather_columns_impl(xc, words, 0, p, tag,
-                                [&](int c, float t) { th_lds[c] = apply_update(c, (int)blockIdx.x * pp + c, t); });
+            gather_columns_impl<8>(xc, words, 0, p, tag,
+                                   [&](int c, float t) { th_lds[c] = apply_update(c, (int)blockIdx.x * pp + c, t); });
             if (s_abort) return true;
         } else {
-            if (sliced_update(xc, words, a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp, th_lds, tag,
+            if (sliced_update<8>(xc, words, a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp, th_lds, tag,
                               [&](int c, float t) { return apply_update(c, c, t); }))
                 return true;
         }
