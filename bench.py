@@ -327,7 +327,7 @@ def main() -> int:
                          "hardware-counter readings of HBM traffic are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the method's step chain is sequential and no "
+        print("bench.py: this library runs on exactly one GPU (the method's step chain is sequential and no "
               "collectives are built); run with --gpus 1", file=sys.stderr)
         return 2
 

@@ -3,7 +3,7 @@
 Algorithm 1 regenerates, at the start of every pass t over buffer S_{r,k}, a
 random partition {S^(t,1), ..., S^(t,M)} of the buffer into mini-batches, and
 Section 2.2 requires the parts to be disjoint and to cover the buffer.  The
-paper does not name a random generator, so this build fixes one (stated in
+paper does not name a random generator, so one is fixed here (stated in
 full below) that needs only 32-bit integer arithmetic and is therefore
 reproducible bit for bit on any machine:
 
@@ -128,7 +128,7 @@ def perm(seed: int, b: int, t: int, N0: int) -> np.ndarray:
     if N0 <= 0:
         return np.empty(0, dtype=np.int32)
     if N0 > (1 << 30):
-        raise ValueError("N0 above 2^30 is outside what this build supports")
+        raise ValueError("N0 above 2^30 is outside the supported range")
     h = half_width(N0)
     keys = round_keys(seed, b, t)
     with np.errstate(over="ignore"):
