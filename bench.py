@@ -119,6 +119,34 @@ def _time_resident(w, bufs, steps, warmup, chain=0):
         ctx.close()
 
 
+def _stream_read_ceiling():
+    """What plain streaming kernels reach on this device: a sum over 1 GiB of fp32 (reads only) and a copy of 1 GiB
+    (reads + writes), library kernels, best of five each, timed with events on the current stream.  Yardsticks beside
+    the published peak, not targets."""
+    import torch
+    x = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    y = torch.empty_like(x)
+
+    def best_ms(fn):
+        fn()
+        torch.cuda.synchronize()
+        best = 1e9
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        return best
+
+    out = {"sum_1GiB_read_GBs": round((1 << 30) / (best_ms(lambda: x.sum()) * 1e-3) / 1e9, 1),
+           "copy_1GiB_read_plus_write_GBs": round(2 * (1 << 30) / (best_ms(lambda: y.copy_(x)) * 1e-3) / 1e9, 1)}
+    del x, y
+    torch.cuda.empty_cache()
+    return out
+
+
 def _roofline(w, delta, traffic=None):
     import workloads as wl
     per_launch_s = delta["chain_ms"] / 1e3 / max(delta["chain_launches"], 1)
@@ -380,6 +408,8 @@ def main() -> int:
                    "workgroups": delta["n_workgroups"], "threads_per_group": delta["threads_per_group"]},
         "roofline": _roofline(w, delta, traffic),
     }
+    if result["roofline"]["bound"] == "hbm":
+        result["roofline"]["measured_streaming_kernels"] = _stream_read_ceiling()
 
     if not args.no_cpu_baseline:
         base, theta_cpu = _cpu_baseline(w, X, y)
