@@ -82,3 +82,37 @@ def test_no_silent_cpu_path():
         return
     rc, h = B.bmgd_create_ex(_cfg())
     assert rc == B.BMGD_EHIP and h is None
+
+
+def test_null_contexts_and_readers_are_rejected():
+    assert B.bmgd_swa_update(None) == B.BMGD_EINVAL
+    assert B.bmgd_swa_reset(None) == B.BMGD_EINVAL
+    assert B.bmgd_set_row_subset(None, None, 0) == B.BMGD_EINVAL
+    assert B.bmgd_run_buffer_adaptive(None, None, None, None, 0, None, 1, 1)[0] == B.BMGD_EINVAL
+    assert B.bmgd_run_buffer_adaptive_reader(None, None, None, None, 1, 1)[0] == B.BMGD_EINVAL
+    assert B.bmgd_load_from_reader(None, None)[0] == B.BMGD_EINVAL
+    assert B.bmgd_reader_acquire(None)[0] == B.BMGD_EINVAL
+    assert B.bmgd_reader_release(None) == B.BMGD_EINVAL
+    assert B.bmgd_reader_stats(None)[0] == B.BMGD_EINVAL
+    B.bmgd_reader_close(None)                   # ignored
+
+
+def test_reader_arguments_are_checked_before_any_device_call(tmp_path):
+    import numpy as np
+    fx, fy = tmp_path / "x.bin", tmp_path / "y.bin"
+    np.zeros((50, 3), dtype=np.float32).tofile(fx)
+    np.zeros(50, dtype=np.float32).tofile(fy)
+    ok = dict(p=3, x_dtype=B.BMGD_F32, n_rows=50, buffer_n=20, ring_slots=2, loop=0)
+    for kw in (dict(p=0), dict(n_rows=0), dict(n_rows=51), dict(buffer_n=0), dict(buffer_n=1 << 30), dict(ring_slots=1),
+               dict(ring_slots=65), dict(x_dtype=3)):
+        a = dict(ok, **kw)
+        rc, h = B.bmgd_reader_open(str(fx), str(fy), a["p"], a["x_dtype"], a["n_rows"], a["buffer_n"], a["ring_slots"], a["loop"])
+        assert rc == B.BMGD_EINVAL and h is None, kw
+        assert B.bmgd_reader_last_error(None) != ""
+    rc, h = B.bmgd_reader_open(str(tmp_path / "nothing.bin"), str(fy), 3, B.BMGD_F32, 50, 20, 2, 0)
+    assert rc == B.BMGD_EINVAL and "cannot open" in B.bmgd_reader_last_error(None)
+    import torch
+    if not torch.cuda.is_available():
+        # the ring is pinned memory from the HIP runtime: without a device the open fails, it does not fall back
+        rc, h = B.bmgd_reader_open(str(fx), str(fy), 3, B.BMGD_F32, 50, 20, 2, 0)
+        assert rc in (B.BMGD_EHIP, B.BMGD_ENOMEM) and h is None
