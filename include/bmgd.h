@@ -137,7 +137,8 @@ typedef struct bmgd_config {
                               stay valid until bmgd_destroy(). */
     size_t   workspace_bytes;
     int32_t  optimizer;    /* BMGD_OPT_*; anything but BMGD_OPT_SGD adds one or two theta-sized state arrays */
-    int32_t  reserved;
+    int32_t  cache_moments; /* 0 / 1: with BMGD_RESHUFFLE_FIXED in the moment form, keep the moment matrices of each of
+                              the n_buffers buffer indices on the device once formed (see bmgd_run_cached_buffer) */
     double   momentum;     /* mu of MOMENTUM / NAG, in [0, 1) */
     double   beta1;        /* Adam, in [0, 1) */
     double   beta2;        /* Adam, in [0, 1) */
@@ -219,6 +220,18 @@ int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream);
  * loaded. */
 int bmgd_run_buffer_adaptive(bmgd_ctx* ctx, void* compute_stream, const void* next_host_x, const void* next_host_y,
                              int64_t next_rows, void* copy_stream, int min_passes, int max_passes, int* passes_done);
+
+/* ---- Fixed partitions: moment matrices formed once (Section 3.1.1 fixes the buffers and their partitions for all
+ * iterations, and eq. (3.1) then needs of a mini-batch only its two moment matrices) --------------------------------
+ * With cache_moments = 1 (least squares in the moment form, BMGD_RESHUFFLE_FIXED, n_buffers = K >= 1) the first run over
+ * buffer index k = b mod K forms the moment matrices of its M mini-batches and keeps them (K * M * (p + 1) * roundup(p, 4)
+ * floats of device memory); every later run over index k is the chain of updates alone and reads no row.  The caller
+ * promises that index k holds the same rows in every iteration.  Such later runs may be made with any run call (the
+ * rows passed are then ignored) or with bmgd_run_cached_buffer, which needs no rows at all: no copy, no slot.
+ * bmgd_run_cached_buffer returns BMGD_ESTATE if the next index is not cached yet.  A run with a row subset set does
+ * not use the cache.  bmgd_clear_moment_cache (blocks) forgets all cached matrices, e.g. before new data. */
+int bmgd_run_cached_buffer(bmgd_ctx* ctx, void* compute_stream);
+int bmgd_clear_moment_cache(bmgd_ctx* ctx);
 
 /* ---- Running on part of a buffer (Section 4.2: for data with few positive responses the negative instances of
  * each buffer are undersampled, so that mini-batches are roughly balanced) ---------------------------------------

@@ -26,7 +26,7 @@ BMGD_OPT_SGD, BMGD_OPT_MOMENTUM, BMGD_OPT_NAG, BMGD_OPT_ADAM = 0, 1, 2, 3
 
 EXPORTS = [
     "bmgd_default_config", "bmgd_create", "bmgd_create_ex", "bmgd_workspace_bytes",
-    "bmgd_set_row_subset", "bmgd_swa_update", "bmgd_get_swa", "bmgd_swa_reset",
+    "bmgd_run_cached_buffer", "bmgd_clear_moment_cache", "bmgd_set_row_subset", "bmgd_swa_update", "bmgd_get_swa", "bmgd_swa_reset",
     "bmgd_reader_open", "bmgd_reader_acquire", "bmgd_reader_release", "bmgd_load_from_reader", "bmgd_run_buffer_adaptive_reader", "bmgd_reader_stats",
     "bmgd_reader_last_error", "bmgd_reader_close",
     "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_buffer_adaptive", "bmgd_run_device_buffer", "bmgd_get_theta",
@@ -41,7 +41,7 @@ class bmgd_config(C.Structure):
         ("passes", C.c_int32), ("model", C.c_int32), ("n_classes", C.c_int32), ("x_dtype", C.c_int32),
         ("seed", C.c_uint64), ("reshuffle", C.c_int32), ("n_buffers", C.c_int32), ("chain", C.c_int32),
         ("n_workgroups", C.c_int32), ("barrier_timeout_us", C.c_int64), ("workspace", C.c_void_p),
-        ("workspace_bytes", C.c_size_t), ("optimizer", C.c_int32), ("reserved", C.c_int32),
+        ("workspace_bytes", C.c_size_t), ("optimizer", C.c_int32), ("cache_moments", C.c_int32),
         ("momentum", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
     ]
 
@@ -75,6 +75,8 @@ def _load() -> C.CDLL:
     lib.bmgd_run_device_buffer.argtypes, lib.bmgd_run_device_buffer.restype = [vp, vp, vp, i64, vp], i32
     lib.bmgd_run_buffer_adaptive.argtypes = [vp, vp, vp, vp, i64, vp, C.c_int, C.c_int, C.POINTER(C.c_int)]
     lib.bmgd_run_buffer_adaptive.restype = i32
+    lib.bmgd_run_cached_buffer.argtypes, lib.bmgd_run_cached_buffer.restype = [vp, vp], i32
+    lib.bmgd_clear_moment_cache.argtypes, lib.bmgd_clear_moment_cache.restype = [vp], i32
     lib.bmgd_set_row_subset.argtypes, lib.bmgd_set_row_subset.restype = [vp, vp, i64], i32
     lib.bmgd_swa_update.argtypes, lib.bmgd_swa_update.restype = [vp, vp], i32
     lib.bmgd_get_swa.argtypes, lib.bmgd_get_swa.restype = [vp, vp, i64, C.POINTER(i64)], i32
@@ -239,6 +241,14 @@ class BmgdError(RuntimeError):
         self.code = code
 
 
+def bmgd_run_cached_buffer(ctx, compute_stream=None) -> int:
+    return lib.bmgd_run_cached_buffer(ctx, _stream(compute_stream))
+
+
+def bmgd_clear_moment_cache(ctx) -> int:
+    return lib.bmgd_clear_moment_cache(ctx)
+
+
 def bmgd_set_row_subset(ctx, dev_idx, count) -> int:
     return lib.bmgd_set_row_subset(ctx, _ptr(dev_idx), count)
 
@@ -360,7 +370,7 @@ class Context:
     def __init__(self, p, buffer_n, batch_n, lr, passes, model=BMGD_LINEAR, n_classes=1, x_dtype=None,
                  seed=0, reshuffle=BMGD_RESHUFFLE_PER_PASS, n_buffers=0, chain=BMGD_CHAIN_AUTO,
                  n_workgroups=0, barrier_timeout_us=0, workspace=None, workspace_bytes=0, optimizer=BMGD_OPT_SGD,
-                 momentum=0.9, beta1=0.9, beta2=0.999, eps=1e-8):
+                 momentum=0.9, beta1=0.9, beta2=0.999, eps=1e-8, cache_moments=False):
         cfg = bmgd_default_config()
         cfg.p, cfg.buffer_n, cfg.batch_n, cfg.lr, cfg.passes = p, buffer_n, batch_n, lr, passes
         cfg.model, cfg.n_classes = model, n_classes
@@ -368,6 +378,7 @@ class Context:
         cfg.seed, cfg.reshuffle, cfg.n_buffers = seed, reshuffle, n_buffers
         cfg.chain, cfg.n_workgroups, cfg.barrier_timeout_us = chain, n_workgroups, barrier_timeout_us
         cfg.optimizer, cfg.momentum, cfg.beta1, cfg.beta2, cfg.eps = optimizer, momentum, beta1, beta2, eps
+        cfg.cache_moments = 1 if cache_moments else 0
         if workspace is not None:
             cfg.workspace, cfg.workspace_bytes = _ptr(workspace), workspace_bytes
         self.cfg = cfg
@@ -394,6 +405,12 @@ class Context:
                                             min_passes, max_passes)
         self._check(rc)
         return done
+
+    def run_cached_buffer(self, compute_stream=None):
+        self._check(bmgd_run_cached_buffer(self.h, compute_stream))
+
+    def clear_moment_cache(self):
+        self._check(bmgd_clear_moment_cache(self.h))
 
     def set_row_subset(self, dev_idx, count):
         """Restrict the next run to rows dev_idx[:count] (an int32 device tensor) of its buffer."""

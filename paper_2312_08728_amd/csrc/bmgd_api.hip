@@ -25,7 +25,7 @@ constexpr int kMaxGroups = 256;                    // upper bound used to size t
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, opt_m, opt_s, opt_len, eval, swa, total;
+    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, gram_cache, gram_cache_set, opt_m, opt_s, opt_len, eval, swa, total;
 };
 
 struct Slot {
@@ -76,6 +76,14 @@ struct bmgd_ctx {
     // buffer overlaps the chain of this one; two sets of partitions and matrices alternate.
     float* gram[2] = {nullptr, nullptr};
     int32_t* gram_perm[2] = {nullptr, nullptr};
+    struct CachedMoments {                         // moment matrices of buffer index k under its fixed partition
+        bool valid = false;
+        int64_t rows = 0;
+        hipEvent_t ready = nullptr;                // completes when the kernel that formed them has
+    };
+    std::vector<CachedMoments> mcache;             // [n_buffers] when cfg.cache_moments
+    char* gram_cache = nullptr;
+    hipEvent_t cache_chain_done = nullptr;         // behind the latest chain that read the cache
     hipStream_t chain_stream = nullptr;
     hipEvent_t prep_done[2] = {nullptr, nullptr};  // stop event of the moment kernel that filled set i (owned by open_prep)
     hipEvent_t chain_done[2] = {nullptr, nullptr}; // stop event of the chain that read set i last (owned by open_chain)
@@ -145,6 +153,13 @@ bool valid_config(const bmgd_config& c, std::string* why)
     if (c.n_workgroups < 0 || c.n_workgroups > kMaxGroups) return bad("n_workgroups must be in [0, 256]");
     if (c.barrier_timeout_us < 0) return bad("barrier_timeout_us must be non-negative");
     if (c.optimizer < BMGD_OPT_SGD || c.optimizer > BMGD_OPT_ADAM) return bad("unknown optimizer");
+    if (c.cache_moments != 0 && c.cache_moments != 1) return bad("cache_moments must be 0 or 1");
+    if (c.cache_moments) {
+        if (c.reshuffle != BMGD_RESHUFFLE_FIXED || c.n_buffers < 1 || c.n_buffers > 65536)
+            return bad("cache_moments needs BMGD_RESHUFFLE_FIXED and 1 <= n_buffers <= 65536");
+        if (c.model != BMGD_LINEAR || c.p > kGramMaxP || (c.chain != BMGD_CHAIN_GRAM && !(c.chain == BMGD_CHAIN_AUTO && c.batch_n >= 2 * c.p)))
+            return bad("cache_moments needs the moment form (BMGD_CHAIN_GRAM, or BMGD_CHAIN_AUTO with batch_n >= 2 p)");
+    }
     if (c.optimizer == BMGD_OPT_MOMENTUM || c.optimizer == BMGD_OPT_NAG) {
         if (!(c.momentum >= 0.0 && c.momentum < 1.0)) return bad("momentum must be in [0, 1)");
     }
@@ -205,6 +220,13 @@ Layout make_layout(const bmgd_config& c)
         l.gram[0] = off; off += set;
         l.gram[1] = off; off += set;
         l.gram_perm = off; off += align_up((size_t)kMaxPassesPerLaunch * c.buffer_n * 4);   // second set of partitions
+    }
+    // moment matrices kept per buffer index (fixed partitions, cache_moments): n_buffers sets of one pass each
+    l.gram_cache = off;
+    l.gram_cache_set = 0;
+    if (c.cache_moments) {
+        l.gram_cache_set = align_up((size_t)((c.buffer_n + c.batch_n - 1) / c.batch_n) * gram_bytes_per_batch(c.p));
+        off += l.gram_cache_set * (size_t)c.n_buffers;
     }
     // optimizer state: like theta; with the redundant reduction every workgroup keeps a private copy (G * p <= 4096
     // words there, rows padded to 16)
@@ -397,6 +419,40 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
         for (int i = 0; i < nperm; ++i) perm_round_keys(c.seed, b, fixed ? 0u : (uint32_t)(t0 + i + 1), keys.key[i]);
         hipEvent_t ev0 = take_event(ctx), ev1 = take_event(ctx);
         if (!ev0 || !ev1) return fail(ctx, BMGD_EHIP, "could not create events");
+        if (ctx->chain == BMGD_CHAIN_GRAM && c.cache_moments && !ctx->subset) {
+            // Fixed partitions: the moment matrices of buffer index b are the same in every iteration (Section 3.1.1),
+            // so they are formed once and every later run over that buffer is the chain alone.
+            bmgd_ctx::CachedMoments& ce = ctx->mcache[b];
+            float* set = reinterpret_cast<float*>(ctx->gram_cache + (size_t)b * ctx->lay.gram_cache_set);
+            if (!ce.valid || ce.rows != rows) {
+                if (!x || !y) return fail(ctx, BMGD_ESTATE, "the moment matrices of this buffer are not cached yet");
+                if (!ce.ready) HIP_TRY(ctx, hipEventCreateWithFlags(&ce.ready, hipEventDisableTiming));
+                hipEvent_t pv0 = take_event(ctx), pv1 = take_event(ctx);
+                if (!pv0 || !pv1) return fail(ctx, BMGD_EHIP, "could not create events");
+                ctx->open_prep.emplace_back(pv0, pv1);
+                // a chain that still reads the old matrices of this index (another row count) must have finished
+                if (ce.valid) HIP_TRY(ctx, hipStreamWaitEvent(stream, ctx->cache_chain_done, 0));
+                HIP_TRY(ctx, launch_perm(ctx->gram_perm[0], rows, 1, keys, stream));
+                HIP_TRY(ctx, gram_launch_moments(static_cast<const float*>(x), static_cast<const float*>(y), ctx->gram_perm[0], set,
+                                                 (int)rows, (int)c.p, (int)n, np, 0, stream, pv0, pv1));
+                HIP_TRY(ctx, hipEventRecord(ce.ready, stream));
+                ce.valid = true;
+                ce.rows = rows;
+            }
+            HIP_TRY(ctx, hipStreamWaitEvent(ctx->chain_stream, ce.ready, 0));
+            HIP_TRY(ctx, gram_launch_chain(set, ctx->theta, (int)rows, (int)c.p, (int)n, np, 0, (float)c.lr,
+                                           lr_len ? ctx->lr_tab_dev : nullptr,
+                                           (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0)), lr_len, opt_args(ctx, 0),
+                                           ctx->chain_stream, ev0, ev1));
+            if (!ctx->cache_chain_done) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->cache_chain_done, hipEventDisableTiming));
+            HIP_TRY(ctx, hipEventRecord(ctx->cache_chain_done, ctx->chain_stream));
+            ctx->lr_pos += (int64_t)np * M;
+            ctx->opt_k += (int64_t)np * M;
+            ctx->open_chain.emplace_back(ev0, ev1);
+            *end_event = ev1;
+            if (chunk_end) *chunk_end = ev1;
+            continue;
+        }
         if (ctx->chain == BMGD_CHAIN_GRAM) {
             const int i = ctx->gsel;
             ctx->gsel ^= 1;
@@ -562,6 +618,9 @@ void destroy_ctx(bmgd_ctx* ctx)
     give_event(ctx, ctx->pending_copy.copy_start);
     give_event(ctx, ctx->pending_copy.copy_end);
     for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+    for (auto& ce : ctx->mcache)
+        if (ce.ready) (void)hipEventDestroy(ce.ready);
+    if (ctx->cache_chain_done) (void)hipEventDestroy(ctx->cache_chain_done);
     for (Slot& s : ctx->slots) {
         if (s.compute_done) (void)hipEventDestroy(s.compute_done);
     }
@@ -664,6 +723,8 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->xt = base + ctx->lay.xt;
     ctx->gram[0] = reinterpret_cast<float*>(base + ctx->lay.gram[0]);
     ctx->gram[1] = reinterpret_cast<float*>(base + ctx->lay.gram[1]);
+    ctx->gram_cache = base + ctx->lay.gram_cache;
+    if (cfg->cache_moments) ctx->mcache.resize((size_t)cfg->n_buffers);
     ctx->gram_perm[0] = ctx->perm;
     ctx->gram_perm[1] = reinterpret_cast<int32_t*>(base + ctx->lay.gram_perm);
     ctx->swa = reinterpret_cast<float*>(base + ctx->lay.swa);
@@ -681,7 +742,8 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
         CREATE_TRY(hipMemset(ctx->ll_part, 0, ctx->lay.sync - ctx->lay.ll_part));
     }
     // moment matrices: the padding entries of their layout are read (and multiplied by zero) but never written
-    if (ctx->lay.gram_perm > ctx->lay.gram[0]) CREATE_TRY(hipMemset(ctx->gram[0], 0, ctx->lay.gram_perm - ctx->lay.gram[0]));
+    // (also the cached ones)
+    if (ctx->lay.opt_m > ctx->lay.gram[0]) CREATE_TRY(hipMemset(ctx->gram[0], 0, ctx->lay.opt_m - ctx->lay.gram[0]));
     CREATE_TRY(hipEventCreate(&ctx->base));
     CREATE_TRY(hipEventRecord(ctx->base, nullptr));
 
@@ -909,16 +971,11 @@ BMGD_API int bmgd_run_buffer_adaptive_reader(bmgd_ctx* ctx, void* compute_stream
                         0, reader, min_passes, max_passes, passes_done, next_rows);
 }
 
-BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* compute_stream)
+// A run over rows that are already on the device (or, with dev_x = dev_y = NULL, over a buffer whose moment matrices
+// are cached: then no row is read).
+static int run_resident(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, hipStream_t s)
 {
-    if (!ctx) return BMGD_EINVAL;
-    if (!dev_x || !dev_y) return fail(ctx, BMGD_EINVAL, "dev_x and dev_y must not be NULL");
-    if (rows < 1 || rows >= (int64_t(1) << 30)) return fail(ctx, BMGD_EINVAL, "rows must be in [1, 2^30)");
-    if (rows > ctx->cfg.buffer_n) return fail(ctx, BMGD_EINVAL, "rows must not exceed buffer_n");
-    if ((reinterpret_cast<uintptr_t>(dev_x) % 16) != 0 || (reinterpret_cast<uintptr_t>(dev_y) % 4) != 0)
-        return fail(ctx, BMGD_EINVAL, "device buffers must be at least 16-byte aligned");
     HIP_TRY(ctx, hipSetDevice(ctx->device));
-    hipStream_t s = static_cast<hipStream_t>(compute_stream);
     const int64_t run_rows = rows_of_run(ctx, rows);
     if (run_rows == 0) return BMGD_EINVAL;
     RunRecord rec;
@@ -938,6 +995,36 @@ BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void
     rec.n_prep = (int)(ctx->open_prep.size() - prep0);
     ctx->open_records.push_back(rec);
     return trim_records(ctx);
+}
+
+BMGD_API int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* compute_stream)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!dev_x || !dev_y) return fail(ctx, BMGD_EINVAL, "dev_x and dev_y must not be NULL");
+    if (rows < 1 || rows >= (int64_t(1) << 30)) return fail(ctx, BMGD_EINVAL, "rows must be in [1, 2^30)");
+    if (rows > ctx->cfg.buffer_n) return fail(ctx, BMGD_EINVAL, "rows must not exceed buffer_n");
+    if ((reinterpret_cast<uintptr_t>(dev_x) % 16) != 0 || (reinterpret_cast<uintptr_t>(dev_y) % 4) != 0)
+        return fail(ctx, BMGD_EINVAL, "device buffers must be at least 16-byte aligned");
+    return run_resident(ctx, dev_x, dev_y, rows, static_cast<hipStream_t>(compute_stream));
+}
+
+BMGD_API int bmgd_run_cached_buffer(bmgd_ctx* ctx, void* compute_stream)
+{
+    if (!ctx) return BMGD_EINVAL;
+    if (!ctx->cfg.cache_moments) return fail(ctx, BMGD_ESTATE, "the context was created without cache_moments");
+    if (ctx->subset) return fail(ctx, BMGD_ESTATE, "a row subset is set: cached moment matrices cover whole buffers");
+    const bmgd_ctx::CachedMoments& ce = ctx->mcache[(size_t)(ctx->buffer_counter % ctx->cfg.n_buffers)];
+    if (!ce.valid) return fail(ctx, BMGD_ESTATE, "the moment matrices of this buffer are not cached yet");
+    return run_resident(ctx, nullptr, nullptr, ce.rows, static_cast<hipStream_t>(compute_stream));
+}
+
+BMGD_API int bmgd_clear_moment_cache(bmgd_ctx* ctx)
+{
+    if (!ctx) return BMGD_EINVAL;
+    const int rc = drain(ctx);                           // no chain may still be reading them
+    if (rc != BMGD_OK) return rc;
+    for (auto& ce : ctx->mcache) ce.valid = false;
+    return BMGD_OK;
 }
 
 BMGD_API int bmgd_eval_loss(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* stream, double* host_out)
