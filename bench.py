@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
 # HBM traffic of one launch of the chain kernel on the primary workload, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE (see profiles/); only valid for the kernel source it was measured on.
-TRAFFIC = {"cfg2": {"kernel_sha256": "d500e824d013915e36c1a3d82ab55a8b22807238c1f2dd7923a9b196664feb56", "bytes_per_launch": 178920098}}
+TRAFFIC = {"cfg2": {"kernel_sha256": "6e2d5ba4b95f6e34319bea1b4eda3da2d65da7e0bf060850707d46c49546f2a5", "bytes_per_launch": 178920811}}
 
 
 def _kernel_sha() -> str:
