@@ -4,9 +4,12 @@ import ctypes
 import os
 import re
 
+import pytest
+
 import paper_2312_08728_amd as B
 
-HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "bmgd.h")
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "bmgd.h")
 
 
 def _declared():
@@ -116,3 +119,31 @@ def test_reader_arguments_are_checked_before_any_device_call(tmp_path):
         # the ring is pinned memory from the HIP runtime: without a device the open fails, it does not fall back
         rc, h = B.bmgd_reader_open(str(fx), str(fy), 3, B.BMGD_F32, 50, 20, 2, 0)
         assert rc in (B.BMGD_EHIP, B.BMGD_ENOMEM) and h is None
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/bmgd.h must be usable from C (C99, pedantic) and C++; a C program that only needs host-side entry points
+    links against libbmgd.so and runs without a device."""
+    import shutil
+    import subprocess
+    src = tmp_path / "use.c"
+    src.write_text('#include "bmgd.h"\n#include <stdio.h>\n'
+                   'int main(void) {\n'
+                   '    bmgd_config c;\n    bmgd_default_config(&c);\n'
+                   '    c.p = 100; c.buffer_n = 1000; c.batch_n = 100; c.lr = 0.1; c.passes = 2;\n'
+                   '    printf("%lu %d\\n", (unsigned long)bmgd_workspace_bytes(&c), bmgd_sync(NULL));\n'
+                   '    return 0;\n}\n')
+    inc = os.path.join(ROOT, "include")
+    gcc = shutil.which("gcc")
+    gxx = shutil.which("g++")
+    if not gcc or not gxx:
+        pytest.skip("no host compiler")
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    subprocess.run([gxx, "-std=c++11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)],
+                   check=True)
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lbmgd", "-Wl,-rpath," + libdir,
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == B.bmgd_workspace_bytes(_cfg()) and int(out[1]) == B.BMGD_EINVAL
