@@ -114,6 +114,18 @@ def test_wide_rows_two_rows_in_flight(model, p, n, G):
     assert np.array_equal(got, again)
 
 
+def test_wide_rows_one_step_per_launch_and_one_row_per_wavefront():
+    """The smallest launches of the wide-row kernel: a single mini-batch per buffer and pass (the refill two groups ahead
+    then always points past the launch), and batches smaller than the number of row slots."""
+    for p, N0, n, T, G in ((4096, 1500, 1500, 1, 8), (2048, 600, 600, 2, 16), (4096, 40, 40, 1, 2), (1028, 100, 7, 3, 4)):
+        w = _case(wl.LINEAR, 2 * N0, p, N0, n, T=T, R=2, alpha=0.2 / p, x_cov="identity")
+        X, y = wl.dataset(w)
+        want = oracle_run(w, X, y)
+        got, st = gpu_run(w, X, y, n_workgroups=G, chain=1)
+        assert st.threads_per_group == 512 and st.n_workgroups == G
+        assert rel_l2(got, want) <= TOL, (p, N0, n, T, G)
+
+
 def test_edge_cases():
     for N, N0, n in [(1, 1, 1), (5, 5, 8), (64, 64, 64), (65, 64, 64), (1000, 1000, 1000), (999, 500, 1)]:
         w = _case(wl.LINEAR, N, 6, N0, min(n, N0), T=3, R=2, alpha=0.05, x_cov="identity")
