@@ -183,9 +183,9 @@ bmgd_ctx* bmgd_create(int64_t p, int64_t buffer_n, int64_t batch_n, double lr, i
 int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out);
 
 /* Device bytes a context with this configuration needs (two buffer slots, partitions, theta and its running
- * average, optimizer state, scratch; in
- * BMGD_CHAIN_GRAM mode also 4 * ceil(buffer_n / batch_n) * (p + 1) * roundup(p, 4) floats of moment matrices);
- * 0 if the configuration is invalid.  Needs no GPU. */
+ * average, optimizer state, scratch; in BMGD_CHAIN_GRAM mode also two sets of moment matrices of
+ * 4 * ceil(buffer_n / batch_n) * (p + 1) * roundup(p, 4) floats each, and with cache_moments n_buffers more of a
+ * quarter of that size); 0 if the configuration is invalid.  Needs no GPU. */
 size_t bmgd_workspace_bytes(const bmgd_config* cfg);
 
 /* Buffering step (Section 2.1; Algorithm 1's "start preparing buffered data"): enqueue on copy_stream the
