@@ -123,3 +123,53 @@ def test_argument_errors():
         assert rc == B.BMGD_ESTATE                      # the buffer has been consumed
     finally:
         ctx.close()
+
+
+def test_adaptive_run_on_a_row_subset_and_with_cached_moments():
+    """A row subset holds for the whole adaptive run (every pass partitions the same listed rows) and for that run only;
+    with cached moment matrices an adaptive run is a sequence of one-pass chains."""
+    import torch
+    import paper_2312_08728_amd as B
+    from oracle import bmgd as O
+    w = _case(wl.LINEAR, 8000, 24, 4000, 250, 1, 0.02)
+    X, y = wl.dataset(w)
+    rng = np.random.default_rng(3)
+    sel = np.sort(rng.choice(4000, size=1700, replace=False)).astype(np.int32)
+    xp, yp = torch.from_numpy(X).pin_memory(), torch.from_numpy(y).pin_memory()
+    sd = torch.from_numpy(sel).cuda()
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx = B.Context(w.p, w.N0, w.n, w.alpha, 1, chain=3)
+    ctx.load_buffer_async(xp[:4000], yp[:4000], 4000, cs)
+    ctx.set_row_subset(sd, 1700)
+    t0 = ctx.run_buffer_adaptive(ks, xp[4000:], yp[4000:], 4000, cs, 3, 3)
+    t1 = ctx.run_buffer_adaptive(ks, None, None, 0, None, 2, 2)
+    got = ctx.get_theta()
+    st = ctx.stats()
+    ctx.close()
+    ref = O.BMGD(w.model, w.p, w.n, w.alpha, 3)
+    ref.run_buffer(X[:4000][sel], y[:4000][sel])
+    ref.T = 2
+    ref.run_buffer(X[4000:], y[4000:])
+    assert (t0, t1) == (3, 2) and st.steps == 3 * 7 + 2 * 16
+    assert rel_l2(got, ref.theta) <= TOL
+
+    # fixed partitions, cached matrices: adaptive runs with a fixed count against plain runs, bit for bit
+    res = []
+    for adaptive in (False, True):
+        ctx = B.Context(w.p, w.N0, w.n, w.alpha, 2, chain=3, reshuffle=1, n_buffers=2, cache_moments=True)
+        for r in range(3):
+            for k in range(2):
+                lo = k * 4000
+                if adaptive:
+                    if r == 0 and k == 0:
+                        ctx.load_buffer_async(xp[lo:lo + 4000], yp[lo:lo + 4000], 4000, cs)
+                    nk = (k + 1) % 2
+                    last = r == 2 and k == 1
+                    ctx.run_buffer_adaptive(ks, None if last else xp[nk * 4000:(nk + 1) * 4000],
+                                            None if last else yp[nk * 4000:(nk + 1) * 4000], 0 if last else 4000, cs, 2, 2)
+                else:
+                    ctx.load_buffer_async(xp[lo:lo + 4000], yp[lo:lo + 4000], 4000, cs)
+                    ctx.run_buffer(ks)
+        res.append((ctx.get_theta(), ctx.stats().prep_launches))
+        ctx.close()
+    assert np.array_equal(res[0][0], res[1][0]) and res[0][1] == res[1][1] == 2

@@ -125,3 +125,29 @@ def test_adaptive_passes_fed_by_the_reader(tmp_path, chain, max_passes):
         ref.T = T
         ref.run_buffer(X[k * 10_000:(k + 1) * 10_000], y[k * 10_000:(k + 1) * 10_000])
     assert rel_l2(got, ref.theta) <= 1e-4, used
+
+
+def test_softmax_buffers_from_bf16_files(tmp_path):
+    """bf16 predictors and int32 class ids through the reader: same estimate, bit for bit, as from pinned memory."""
+    import torch
+    import paper_2312_08728_amd as B
+    w = wl.CONFIGS["cfg5"].scaled(name="case", N=2500, p=96, C=12, N0=1000, n=256, T=1, R=1)
+    X, y = wl.dataset(w)                                       # uint16 bit patterns of bf16, int32 labels
+    fx, fy = _files(tmp_path, X, y)
+    want, _ = gpu_run(w, X, y)
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx = B.Context(w.p, w.N0, w.n, w.alpha, w.T, model=w.model, n_classes=w.C, n_buffers=3)
+    rd = B.Reader(fx, fy, w.p, w.N, w.N0, x_dtype=B.BMGD_BF16, ring_slots=2)
+    rows = []
+    while True:
+        r = rd.load_into(ctx, cs)
+        if r == 0:
+            break
+        rows.append(r)
+        ctx.run_buffer(ks)
+    got = ctx.get_theta()
+    rd.close()
+    ctx.close()
+    assert rows == [1000, 1000, 500]
+    assert np.array_equal(got, want)
+    assert rel_l2(got, oracle_run(w, X, y)) <= 2e-3
