@@ -97,7 +97,7 @@ def test_fixed_partitions_and_adam():
         ref.T = T
         ref.run_buffer(X[k * 10_000:(k + 1) * 10_000], y[k * 10_000:(k + 1) * 10_000])
     assert all(2 <= u <= 5 for u in used)
-    assert rel_l2(theta, ref.theta) <= 5e-4, used
+    assert rel_l2(theta, ref.theta) <= TOL, used
 
 
 def test_argument_errors():

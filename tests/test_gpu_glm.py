@@ -28,6 +28,32 @@ def test_cfg1_full_run():
         assert rel_l2(got, want) <= TOL
 
 
+def test_the_four_calls_with_defaults():
+    """bmgd_create(p, buffer_n, batch_n, lr, passes) with every default (least squares, fp32, seed 0, a new partition
+    per pass, theta = 0, automatic chain, default stream), then only bmgd_load_buffer_async, bmgd_run_buffer and
+    bmgd_get_theta, called as plain C entry points, against the oracle."""
+    import torch
+    import paper_2312_08728_amd as B
+    from oracle import bmgd as O
+    for p, N0, n, lr, T in ((12, 3000, 250, 0.05, 2), (300, 5000, 999, 0.002, 3)):
+        w = _case(wl.LINEAR, 3 * N0 - 77, p, N0, n, T, 1, lr, x_cov="identity")
+        X, y = wl.dataset(w)
+        xp, yp = torch.from_numpy(X).pin_memory(), torch.from_numpy(y).pin_memory()
+        h = B.bmgd_create(p, N0, n, lr, T)
+        assert h, B.bmgd_last_error(None)
+        try:
+            st = O.BMGD(O.LINEAR, p, n, lr, T)
+            out = np.empty(p, dtype=np.float32)
+            for k in range(w.K):
+                lo, hi = wl.buffer_rows(w, k)
+                assert B.bmgd_load_buffer_async(h, xp[lo:hi], yp[lo:hi], hi - lo) == B.BMGD_OK
+                assert B.bmgd_run_buffer(h) == B.BMGD_OK
+                assert B.bmgd_get_theta(h, out, p) == B.BMGD_OK
+                assert rel_l2(out, st.run_buffer(X[lo:hi], y[lo:hi])) <= TOL, (p, k)
+        finally:
+            B.bmgd_destroy(h)
+
+
 # p chosen to hit every vector width / lanes-per-row / chunks-per-lane combination, with ragged batches
 SHAPES = [
     # model, p, N0, n
