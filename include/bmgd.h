@@ -343,6 +343,23 @@ int bmgd_get_perm(bmgd_ctx* ctx, int64_t buffer_counter, int pass, int32_t* host
  * fp64 sums in a fixed order.  dev_x, dev_y, rows as for bmgd_run_device_buffer (rows may exceed buffer_n).  Blocks. */
 int bmgd_eval_loss(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, void* stream, double* host_out);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the mean loss of bmgd_eval_loss for the least-squares and logistic models, without a context.
+ * The per-workgroup partial sums go to a static device array of the library (1024 doubles = 8 KiB on every device the
+ * library runs on, held until the process ends) instead of a context's workspace, and the result is left in device
+ * memory: the call enqueues two kernels on `stream` and nothing else - no allocation, no copy, no synchronisation.
+ *   model      BMGD_LINEAR or BMGD_LOGISTIC (BMGD_SOFTMAX: BMGD_EINVAL, its logits scratch exceeds the static array)
+ *   dev_x      device, row-major [rows][p] fp32, 16-byte aligned;  dev_y  device, [rows] fp32
+ *   dev_theta  device, [p] fp32: the point at which the loss is evaluated (read in stream order)
+ *   rows       in [1, 2^30);  p in [1, 4096]: larger sizes are rejected with BMGD_EINVAL
+ *   dev_out    device, one double: receives the mean loss when the work on `stream` has run
+ * fp32 per row, fp64 sums in the fixed order of bmgd_eval_loss (same value bit for bit).  The device that is current
+ * at the call is used; `stream` must belong to it.  Every call on one device shares that device's array: calls that
+ * overlap on one device (two streams, two threads) race and must be ordered by the caller; calls in stream order are
+ * safe, and nothing needs clearing between them.  Message of a failure: bmgd_last_error(NULL), per calling thread. */
+int bmgd_eval_loss_static(int32_t model, const float* dev_x, const float* dev_y, const float* dev_theta, int64_t rows,
+                          int64_t p, void* stream, double* dev_out);
+
 /* Wait for all enqueued work (both streams last used) and report a device-side time-out if one happened. */
 int bmgd_sync(bmgd_ctx* ctx);
 

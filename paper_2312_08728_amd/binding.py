@@ -30,7 +30,7 @@ EXPORTS = [
     "bmgd_reader_open", "bmgd_reader_acquire", "bmgd_reader_release", "bmgd_load_from_reader", "bmgd_run_buffer_adaptive_reader", "bmgd_reader_stats",
     "bmgd_reader_last_error", "bmgd_reader_close",
     "bmgd_load_buffer_async", "bmgd_run_buffer", "bmgd_run_buffer_adaptive", "bmgd_run_device_buffer", "bmgd_get_theta",
-    "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_lr_schedule", "bmgd_reset_optimizer", "bmgd_eval_loss", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
+    "bmgd_set_theta", "bmgd_set_lr", "bmgd_set_passes", "bmgd_set_lr_schedule", "bmgd_reset_optimizer", "bmgd_eval_loss", "bmgd_eval_loss_static", "bmgd_set_position", "bmgd_get_perm", "bmgd_sync", "bmgd_get_stats",
     "bmgd_last_error", "bmgd_destroy",
 ]
 
@@ -96,6 +96,8 @@ def _load() -> C.CDLL:
     lib.bmgd_set_position.argtypes, lib.bmgd_set_position.restype = [vp, i64], i32
     lib.bmgd_set_lr.argtypes, lib.bmgd_set_lr.restype = [vp, C.c_double], i32
     lib.bmgd_eval_loss.argtypes, lib.bmgd_eval_loss.restype = [vp, vp, vp, C.c_int64, vp, C.POINTER(C.c_double)], i32
+    lib.bmgd_eval_loss_static.argtypes = [C.c_int32, vp, vp, vp, C.c_int64, C.c_int64, vp, vp]
+    lib.bmgd_eval_loss_static.restype = i32
     lib.bmgd_reset_optimizer.argtypes, lib.bmgd_reset_optimizer.restype = [vp], i32
     lib.bmgd_set_lr_schedule.argtypes, lib.bmgd_set_lr_schedule.restype = [vp, vp, C.c_int64], i32
     lib.bmgd_set_passes.argtypes, lib.bmgd_set_passes.restype = [vp, i32], i32
@@ -193,6 +195,10 @@ def bmgd_eval_loss(ctx, dev_x, dev_y, rows, stream=None):
     out = C.c_double(0.0)
     rc = lib.bmgd_eval_loss(ctx, _ptr(dev_x), _ptr(dev_y), rows, _stream(stream), C.byref(out))
     return rc, out.value
+
+
+def bmgd_eval_loss_static(model, dev_x, dev_y, dev_theta, rows, p, stream, dev_out) -> int:
+    return lib.bmgd_eval_loss_static(model, _ptr(dev_x), _ptr(dev_y), _ptr(dev_theta), rows, p, _stream(stream), _ptr(dev_out))
 
 
 def bmgd_reset_optimizer(ctx) -> int:

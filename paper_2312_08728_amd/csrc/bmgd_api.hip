@@ -19,6 +19,12 @@ namespace {
 
 thread_local std::string g_create_error;
 
+}  // namespace
+
+void bmgd::set_create_error(const char* msg) { g_create_error = msg ? msg : ""; }
+
+namespace {
+
 constexpr size_t kAlign = 256;
 constexpr int kMaxGroups = 256;                    // upper bound used to size the partial-sum scratch
 

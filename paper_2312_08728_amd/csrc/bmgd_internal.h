@@ -12,6 +12,9 @@ int reader_take(bmgd_reader* r, bool block, const void** x, const void** y, int6
 
 namespace bmgd {
 
+// Message that bmgd_last_error(NULL) returns on the calling thread (calls that have no context to hold one).
+void set_create_error(const char* msg);
+
 constexpr int kPermRounds = 8;
 constexpr int kMaxPassesPerLaunch = 4;     // partitions kept on the device at a time
 constexpr int kThetaCopies = 8;            // copies of the theta broadcast (sliced reduction)
