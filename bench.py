@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM traffic of one launch of the chain kernel on the primary workload, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE (see profiles/), scaled by the copy calibration; valid only for the source of the kernel it was measured on
 # (the line reports null once that file has changed: measure again and update the entry).
-TRAFFIC = {"cfg4": {"sources": ("glm_kernels.hip",), "kernel_sha256": "ba4d7dcd053a67dab326edd7fc9b6156b2846da97e2a5f2bcb3427e3ad62575f", "bytes_per_launch": 9364419355}}
+TRAFFIC = {"cfg4": {"sources": ("glm_split_kernel.hip",), "kernel_sha256": "26aae02c8ac2ca4a3de45e88fc878a39d6a76f25ad58578c3026c20aa59d4ded", "bytes_per_launch": 9433322236}}
 
 
 def _kernel_sha(sources) -> str:
@@ -185,8 +185,8 @@ def _roofline(w, delta, traffic=None):
     achieved = bytes_per_launch / per_launch_s / 1e9
     return {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
-            # rows wider than 1024 floats on more than one workgroup run the two-rows-in-flight variant
-            "kernel": "glm_wide_kernel" if w.p > 1024 and w.p % 4 == 0 and delta["n_workgroups"] > 1 else "glm_chain_kernel",
+            # rows wider than 1024 floats on eight or more workgroups run the kernel with an exchange wavefront
+            "kernel": "glm_split_kernel" if w.p > 1024 and w.p % 4 == 0 and delta["n_workgroups"] >= 8 else "glm_chain_kernel",
             "avg_launch_ms": round(per_launch_s * 1e3, 4),
             "algorithmic_bytes_per_launch": int(bytes_per_launch)}
 

@@ -745,7 +745,7 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     } else {
         CREATE_TRY(hipMemset(ctx->theta, 0, (size_t)ctx->theta_len * 4));
         // flagged words start with tag 0, which no step ever waits for
-        CREATE_TRY(hipMemset(ctx->ll_part, 0, ctx->lay.sync - ctx->lay.ll_part));
+        CREATE_TRY(hipMemset(ctx->partial, 0, ctx->lay.sync - ctx->lay.partial));   // (and the arrival flags kept in `partial`)
     }
     // moment matrices: the padding entries of their layout are read (and multiplied by zero) but never written
     // (also the cached ones)
@@ -1251,7 +1251,8 @@ BMGD_API int bmgd_get_stats(bmgd_ctx* ctx, bmgd_stats* out)
     out->wait_ms = ctx->wait_ms;
     const bool one_group = ctx->chain == BMGD_CHAIN_GRAM;       // the chain itself runs in a single workgroup
     out->n_workgroups = one_group ? 1 : ctx->shape.G;
-    out->threads_per_group = one_group ? gram_chain_threads(ctx->cfg.p) : ctx->shape.block;
+    out->threads_per_group = one_group ? gram_chain_threads(ctx->cfg.p)
+                             : ctx->chain == BMGD_CHAIN_PERSISTENT ? ctx->shape.chain_block : ctx->shape.block;
     out->chain = ctx->chain;
     out->chain_ms = ctx->chain_ms;
     out->chain_launches = ctx->chain_launches;

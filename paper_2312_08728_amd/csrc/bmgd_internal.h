@@ -94,6 +94,10 @@ struct GlmLaunchShape {
     size_t lds_bytes;
     int max_G;          // co-resident workgroups the device can hold for this kernel
     int with_optimizer; // set by the caller after glm_plan: the kernel variant with an update rule other than the plain step
+    int split;          // 1: the persistent chain runs the kernel for rows of more than 1024 floats (glm_split_kernel.hip):
+                        // G is a multiple of 8, split_ch = float4 chunks of a row per lane (1: p <= 2048, 2: p <= 4096)
+    int split_ch;
+    int chain_block;    // threads per workgroup of the persistent chain's kernel
 };
 
 struct GlmArgs {
@@ -129,6 +133,13 @@ hipError_t glm_prepare(GlmLaunchShape* shape);
 hipError_t glm_launch_chain(const GlmLaunchShape& shape, const GlmArgs& args, hipStream_t stream);
 // Step-per-launch variant: partial sums for step `args.single_step`, then reduce + update.
 hipError_t glm_launch_step(const GlmLaunchShape& shape, const GlmArgs& args, int nb, hipStream_t stream);
+
+// Persistent chain for rows of more than 1024 floats on G = 8, 16, ... workgroups (glm_split_kernel.hip): shared memory
+// and threads per workgroup, co-resident capacity, one launch covering steps [s_begin, s_end).
+size_t glm_split_lds_bytes(int ch);
+int glm_split_block();
+hipError_t glm_split_prepare(int ch, bool opt, int* max_groups);
+hipError_t glm_split_launch(int ch, bool opt, int G, const GlmArgs& args, hipStream_t stream);
 
 // Evaluation: partial[b] = sum of the per-sample losses of the rows workgroup b takes (b < nblocks <= kEvalBlocks).
 constexpr int kEvalBlocks = 1024;

@@ -23,6 +23,7 @@
 //   sliced     workgroup g sums a slice of the columns, writes that slice of theta, second barrier, all
 //              re-read theta (for large p).
 #include "bmgd_internal.h"
+#include "glm_device.h"
 
 #include <stdio.h>
 
@@ -31,167 +32,6 @@
 namespace bmgd {
 
 namespace {
-
-enum { kLinear = 0, kLogistic = 1 };
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_mov(float v)
-{
-    return __builtin_bit_cast(float,
-                              __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-
-// lane i of an even 16-lane row + lane i of the odd row next to it, result in both
-__device__ __forceinline__ float swap16_sum(float v)
-{
-    // Both registers are rewritten by the instruction, so it is issued as inline assembly with two
-    // read-write operands (the compiler builtin hands back only one of the two results).  The s_nop
-    // covers the wait states the instruction needs after a VALU write of its operands.
-    float a = v, b = v;
-    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
-    return a + b;
-}
-
-// lane i of the lower half-wave + lane i of the upper half-wave, result in both
-__device__ __forceinline__ float swap32_sum(float v)
-{
-    // Both registers are rewritten by the instruction, so it is issued as inline assembly with two
-    // read-write operands (the compiler builtin hands back only one of the two results).  The s_nop
-    // covers the wait states the instruction needs after a VALU write of its operands.
-    float a = v, b = v;
-    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
-    return a + b;
-}
-
-// Sum over each aligned group of L consecutive lanes; every lane of the group receives the sum.
-__device__ __forceinline__ float group_sum(float v, int L)
-{
-    if (L >= 2) v += dpp_mov<0xB1>(v);    // quad_perm [1,0,3,2]
-    if (L >= 4) v += dpp_mov<0x4E>(v);    // quad_perm [2,3,0,1]
-    if (L >= 8) v += dpp_mov<0x141>(v);   // row_half_mirror (both quads already hold their sums)
-    if (L >= 16) v += dpp_mov<0x140>(v);  // row_mirror
-    if (L >= 32) v = swap16_sum(v);
-    if (L >= 64) v = swap32_sum(v);
-    return v;
-}
-
-// Sum over the lanes that share lane % L (one per row slot of the wavefront); valid in lanes < L.
-__device__ __forceinline__ float slot_sum(float v, int L)
-{
-    if (L <= 1) v += dpp_mov<0x121>(v);   // row_ror 1
-    if (L <= 2) v += dpp_mov<0x122>(v);   // row_ror 2
-    if (L <= 4) v += dpp_mov<0x124>(v);   // row_ror 4
-    if (L <= 8) v += dpp_mov<0x128>(v);   // row_ror 8
-    if (L <= 16) v = swap16_sum(v);
-    if (L <= 32) v = swap32_sum(v);
-    return v;
-}
-
-template <int V>
-__device__ __forceinline__ void load_vec(const float* __restrict__ src, float* dst)
-{
-    if constexpr (V == 4) {
-        const float4 t = *reinterpret_cast<const float4*>(src);
-        dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w;
-    } else if constexpr (V == 2) {
-        const float2 t = *reinterpret_cast<const float2*>(src);
-        dst[0] = t.x; dst[1] = t.y;
-    } else {
-        dst[0] = *src;
-    }
-}
-
-__device__ __forceinline__ float residual(int model, float u, float y)
-{
-    if (model == kLogistic) {
-        const float e = expf(-fabsf(u));
-        const float s = (u >= 0.f) ? 1.f / (1.f + e) : e / (1.f + e);
-        return s - y;
-    }
-    return u - y;
-}
-
-// Exchange between workgroups: "flagged words".  A value travels as one 64-bit word {tag : float bits}
-// written with a single 8-byte store; a reader polls the word until it carries the tag of the step it
-// waits for.  Data and readiness arrive together, so a step needs no separate barrier, fence or counter.
-// Tags grow monotonically over the life of a context and 0 is never used, hence stale words never match.
-__device__ __forceinline__ void ll_store(unsigned long long* dst, float v, unsigned tag)
-{
-    const unsigned long long w = ((unsigned long long)tag << 32) | (unsigned long long)__builtin_bit_cast(unsigned, v);
-    __hip_atomic_store(dst, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ unsigned long long ll_load(const unsigned long long* src)
-{
-    return __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Four flagged words requested back to back and awaited together.  (Written as inline assembly because
-// the compiler waits for each atomic load before issuing the next; the instruction is the one it emits
-// for an agent-scope load.)  The wait also covers this wavefront's older loads.
-__device__ __forceinline__ void ll_load4(const unsigned long long* const (&src)[4], unsigned long long (&w)[4])
-{
-    asm volatile("global_load_dwordx2 %0, %4, off sc1\n\t"
-                 "global_load_dwordx2 %1, %5, off sc1\n\t"
-                 "global_load_dwordx2 %2, %6, off sc1\n\t"
-                 "global_load_dwordx2 %3, %7, off sc1\n\t"
-                 "s_waitcnt vmcnt(0)"
-                 : "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]), "=&v"(w[3])
-                 : "v"(src[0]), "v"(src[1]), "v"(src[2]), "v"(src[3])
-                 : "memory");
-}
-
-// The same with eight words per trip (wide rows: a thread has eight words to fetch per exchange, and two trips of four
-// cost twice the latency of the fabric).
-__device__ __forceinline__ void ll_load8(const unsigned long long* const (&src)[8], unsigned long long (&w)[8])
-{
-    asm volatile("global_load_dwordx2 %0, %8, off sc1\n\t"
-                 "global_load_dwordx2 %1, %9, off sc1\n\t"
-                 "global_load_dwordx2 %2, %10, off sc1\n\t"
-                 "global_load_dwordx2 %3, %11, off sc1\n\t"
-                 "global_load_dwordx2 %4, %12, off sc1\n\t"
-                 "global_load_dwordx2 %5, %13, off sc1\n\t"
-                 "global_load_dwordx2 %6, %14, off sc1\n\t"
-                 "global_load_dwordx2 %7, %15, off sc1\n\t"
-                 "s_waitcnt vmcnt(0)"
-                 : "=&v"(w[0]), "=&v"(w[1]), "=&v"(w[2]), "=&v"(w[3]), "=&v"(w[4]), "=&v"(w[5]), "=&v"(w[6]), "=&v"(w[7])
-                 : "v"(src[0]), "v"(src[1]), "v"(src[2]), "v"(src[3]), "v"(src[4]), "v"(src[5]), "v"(src[6]), "v"(src[7])
-                 : "memory");
-}
-
-template <int U>
-__device__ __forceinline__ void ll_load_n(const unsigned long long* const (&src)[U], unsigned long long (&w)[U])
-{
-    static_assert(U == 4 || U == 8, "four or eight words per trip");
-    if constexpr (U == 4) ll_load4(src, w);
-    else ll_load8(src, w);
-}
-
-// Every wait is bounded: a poll that has failed for `timeout` ticks of the 100 MHz wall clock raises the
-// abort flag, which every other poller checks, and the kernel exits.
-struct PollGuard {
-    unsigned* flag;
-    long long timeout;
-    long long t0;
-    unsigned misses;
-    // Called after a failed poll: backs off briefly (polls travel over the fabric; a storm of them slows
-    // the very stores they wait for), and reports true when the wait must be given up.
-    __device__ __forceinline__ bool expired()
-    {
-        __builtin_amdgcn_s_sleep(2);
-        ++misses;
-        if (misses > 2u && (misses & 31u) != 0u) return false;   // clock and flag: first misses, then every 32nd
-        if (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return true;
-        const long long now = wall_clock64();
-        if (t0 == 0) t0 = now;
-        if (now - t0 > timeout) {
-            __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            return true;
-        }
-        return false;
-    }
-    __device__ __forceinline__ void arm() { t0 = 0; misses = 0; }
-};
 
 // What the cross-workgroup sum needs to know about its caller.
 struct ExchangeCtx {
@@ -576,235 +416,6 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
     }
 }
 
-// Wide rows (1024 < p <= 4096), persistent chain over several workgroups.
-//
-// One wavefront holds one whole row (CPL float4 chunks per lane).  A step is bound by the time HBM needs for its rows,
-// and nothing can be computed between the end of a step's rows and the arrival of the new theta; what can be done in
-// that window is to have the rows of the next step on their way.  So each wavefront keeps TWO rows in flight at all
-// times, in two register sets used in turn over the whole sequence of row groups (s, 0), (s, 1), ..., (s + 1, 0), ...:
-// a set is refilled with the group two places ahead as soon as it has been used, also across a step's end, and half
-// of a four-group step is then loaded while the exchange resolves.  To make room for the second row the gradient
-// sums of a wavefront live in shared memory (its own p floats: plain read-add-write, no atomics) instead of registers.
-// The barrier after a step's last rows waits for shared memory only: rows in flight do not hold it up.
-// (The polls of the exchange still return behind the wavefront's older row loads - loads complete in order -, so
-// the exchange ends no earlier than those rows land; that time is spent loading either way.)
-constexpr int kWideBlock = 512;
-
-__device__ __forceinline__ void lds_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-template <int CPL, bool OPT>
-__global__ void __launch_bounds__(kWideBlock) glm_wide_kernel(GlmArgs a)
-{
-    extern __shared__ __align__(16) float smem[];
-    __shared__ int s_abort;
-
-    constexpr int BLOCK = kWideBlock;
-    constexpr int NW = BLOCK / 64;
-    constexpr int E = CPL * 4;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int G = gridDim.x;
-    const int p = a.p;
-    const int S_total = G * NW;                      // rows per group
-    const int myslot = blockIdx.x * NW + wave;
-    const int pp = (p + 15) & ~15;
-    const int th_len = max((p + 63) & ~63, 256 * CPL);
-    float* th_lds = smem;                            // [th_len]
-    float* wpart = smem + th_len;                    // [NW][p] per-wavefront sums
-    float* red = wpart + NW * p;                     // [BLOCK] scratch of the cross-workgroup sum
-    float* wacc = wpart + wave * p;
-    const int M = (a.rows + a.n - 1) / a.n;
-    const int first = a.s_begin, last = a.s_end;
-
-    for (int c = tid; c < th_len; c += BLOCK) th_lds[c] = c < p ? a.theta[c] : 0.f;
-    if (tid == 0) s_abort = 0;
-    __syncthreads();
-
-    const float rcpM = 1.0f / (float)M;
-    auto split = [&](int s, int& t, int& m) {        // s = t M + m, exact for s < 2^23
-        t = (int)((float)s * rcpM);
-        m = s - t * M;
-        if (m >= M) { m -= M; ++t; }
-        if (m < 0) { m += M; --t; }
-    };
-    const int n_tail = a.rows - (M - 1) * a.n;
-    const int iters_full = (a.n + S_total - 1) / S_total;
-    const int iters_tail = (n_tail + S_total - 1) / S_total;
-    auto batch_rows = [&](int s) { int t, m; split(s, t, m); return m == M - 1 ? n_tail : a.n; };
-    auto batch_base = [&](int s) { int t, m; split(s, t, m); return t * a.perm_stride + m * a.n; };
-    auto batch_iters = [&](int s) { int t, m; split(s, t, m); return m == M - 1 ? iters_tail : iters_full; };
-
-    struct Row {
-        float x[E];
-        float y;
-        bool ok;
-        int idx_next;                                // row this set takes at its next request, and whether that
-        bool ok_next;                                // group has a row for this wavefront at all
-    };
-    Row A, B;
-
-    // Each set carries the index of the row it will request next, loaded right after its previous request: by the
-    // time it is needed it is older than the other set's rows in flight, so waiting for it waits for none of them
-    // (loads complete in order).  Groups beyond the launch read the first step's rows and count as empty.
-    int sq = first, iq = 0;                          // the group whose index is loaded next
-    auto load_idx = [&](Row& r) {
-        const bool live = sq < last;
-        const int sc = live ? sq : first;
-        const int j = iq * S_total + myslot;
-        r.ok_next = live && j < batch_rows(sc);
-        r.idx_next = a.perm[batch_base(sc) + (r.ok_next ? j : 0)];
-        if (live) {
-            if (iq + 1 < batch_iters(sq)) ++iq;
-            else { ++sq; iq = 0; }
-        }
-    };
-    // Request the rows of the set's next group (row `idx`: the set's idx_next, read into a scalar by the caller at
-    // a point where waiting for it costs nothing), then the index for the request after that.
-    auto request = [&](Row& r, int idx) {
-        const float* row = a.X + (size_t)idx * p;
-        r.y = a.y[idx];
-        r.ok = r.ok_next;
-#pragma unroll
-        for (int k = 0; k < CPL; ++k) {
-            const int c = 4 * (lane + 64 * k);
-            const float4 t = *reinterpret_cast<const float4*>(row + (c < p ? c : 0));   // chunks beyond p: theta is 0 there
-            r.x[4 * k] = t.x; r.x[4 * k + 1] = t.y; r.x[4 * k + 2] = t.z; r.x[4 * k + 3] = t.w;
-        }
-        load_idx(r);
-    };
-    load_idx(A);
-    load_idx(B);
-    asm volatile("" ::: "memory");                   // A's rows are the older ones, as in every later round
-    request(A, __builtin_amdgcn_readfirstlane(A.idx_next));
-    asm volatile("" ::: "memory");
-    request(B, __builtin_amdgcn_readfirstlane(B.idx_next));
-    asm volatile("" ::: "memory");
-
-    PollGuard guard{a.sync + 1, a.timeout_ticks, 0, 0};
-    ExchangeCtx xc{G, p, pp, tid, BLOCK, red, &s_abort, &guard};
-
-    int su = first, iu = 0;                          // the group that is used next
-    int iters_u = batch_iters(min(su, last - 1));
-    // learning rate of step su: requested when the step begins, so that it is older than the step's rows and
-    // waiting for it at the step's end waits for none of them
-    auto rate_of = [&](int s) { return a.lr_tab ? a.lr_tab[min(a.lr_base + min(s, last - 1), a.lr_len - 1)] : a.alpha; };
-    float alpha_s = first < last ? rate_of(first) : a.alpha;
-
-    // Use the rows in `r` (group (su, iu)), refill `r`, and end the step if that was its last group.
-    // Returns true when the launch is over (all steps done, or a wait ran out).
-    auto process = [&](Row& r) -> bool {
-        float dot = 0.f;
-#pragma unroll
-        for (int k = 0; k < CPL; ++k) {
-            const float4 t = *reinterpret_cast<const float4*>(th_lds + 4 * (lane + 64 * k));
-            dot = fmaf(r.x[4 * k], t.x, dot);
-            dot = fmaf(r.x[4 * k + 1], t.y, dot);
-            dot = fmaf(r.x[4 * k + 2], t.z, dot);
-            dot = fmaf(r.x[4 * k + 3], t.w, dot);
-        }
-        dot = group_sum(dot, 64);
-        const float res = r.ok ? residual(a.model, dot, r.y) : 0.f;
-        // the set's next row: its index arrived right behind the rows just used (the same for all lanes)
-        const int idx_s = __builtin_amdgcn_readfirstlane(r.idx_next);
-        if (iu == 0) {
-#pragma unroll
-            for (int k = 0; k < CPL; ++k) {
-                const int c = 4 * (lane + 64 * k);
-                if (c < p)
-                    *reinterpret_cast<float4*>(wacc + c) =
-                        make_float4(res * r.x[4 * k], res * r.x[4 * k + 1], res * r.x[4 * k + 2], res * r.x[4 * k + 3]);
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < CPL; ++k) {
-                const int c = 4 * (lane + 64 * k);
-                if (c < p) {
-                    float4 t = *reinterpret_cast<float4*>(wacc + c);
-                    t.x = fmaf(res, r.x[4 * k], t.x);
-                    t.y = fmaf(res, r.x[4 * k + 1], t.y);
-                    t.z = fmaf(res, r.x[4 * k + 2], t.z);
-                    t.w = fmaf(res, r.x[4 * k + 3], t.w);
-                    *reinterpret_cast<float4*>(wacc + c) = t;
-                }
-            }
-        }
-        const bool step_ends = iu + 1 >= iters_u;
-        const int s = su;
-        const unsigned tag = a.tag_base + (unsigned)(s - first) + 1u;
-        unsigned long long* words = a.ll_part + (size_t)(s & 1) * G * pp;
-        if (step_ends) {
-            guard.arm();
-            lds_barrier();
-            // publish this workgroup's sums as flagged words: they are what the others wait for
-            for (int c = tid; c < p; c += BLOCK) {
-                float t = 0.f;
-                for (int w = 0; w < NW; ++w) t += wpart[w * p + c];
-                ll_store(words + (size_t)blockIdx.x * pp + c, t, tag);
-            }
-        }
-        // The refill: one place in the code for both cases, so that what it loads has one home in registers (two
-        // would be reconciled by copies, and a copy of a value in flight waits for everything in flight).  It stays
-        // behind the last use of the set's registers and behind the publication of the sums.
-        asm volatile("" ::: "memory");
-        request(r, idx_s);
-        asm volatile("" ::: "memory");
-        if (!step_ends) {
-            ++iu;
-            return false;
-        }
-
-        // ---- the rest of the end of step su
-        const int nb = batch_rows(s);
-        const float scale = alpha_s / (float)nb;
-        float oc1 = 1.f, oc2 = 1.f;
-        if constexpr (OPT) {
-            if (a.opt.kind == kOptAdam) opt_corrections(a.opt, a.opt.k_base + (s - first) + 1, oc1, oc2);
-        }
-        auto apply_update = [&](int c, int si, float t) -> float {
-            if constexpr (!OPT) return th_lds[c] - scale * t;
-            float m = a.opt.m[si], sv = a.opt.kind == kOptAdam ? a.opt.s[si] : 0.f;
-            const float v = opt_update(a.opt, th_lds[c], t / (float)nb, alpha_s, m, sv, oc1, oc2);
-            a.opt.m[si] = m;
-            if (a.opt.kind == kOptAdam) a.opt.s[si] = sv;
-            return v;
-        };
-        if (a.reduce_mode == kReduceRedundant) {
-            gather_columns_impl<8>(xc, words, 0, p, tag,
-                                   [&](int c, float t) { th_lds[c] = apply_update(c, (int)blockIdx.x * pp + c, t); });
-            if (s_abort) return true;
-        } else {
-            if (sliced_update<8>(xc, words, a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp, th_lds, tag,
-                              [&](int c, float t) { return apply_update(c, c, t); }))
-                return true;
-        }
-        // Everything this wavefront had in flight has landed (the polls waited for it); said in a form the compiler
-        // sees, so that the waits it plans for the next rows start from a clean slate.
-        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0) only
-        ++su;
-        iu = 0;
-        iters_u = batch_iters(min(su, last - 1));
-        alpha_s = rate_of(su);
-        return su >= last;
-    };
-
-    if (first < last) {
-        // (not peeled or unrolled: every round of the loop then finds the two sets in the same order of age)
-#pragma clang loop unroll(disable)
-        for (;;) {
-            if (process(A)) break;
-            if (process(B)) break;
-        }
-    }
-    // rows requested beyond the last step land in registers that die with the wavefront
-    if (blockIdx.x == 0 && !s_abort) {
-        for (int c = tid; c < p; c += BLOCK) a.theta[c] = th_lds[c];
-    }
-}
-
 // Step-per-launch companion: one thread per column sums the workgroups' partial sums and applies the update
 // (opt.k_base = updates made before this one).
 __global__ void __launch_bounds__(256) glm_update_kernel(float* __restrict__ theta, const float* __restrict__ part,
@@ -988,21 +599,19 @@ bool glm_plan(int64_t p, int64_t n, int requested_G, int num_cus, GlmLaunchShape
     } else {
         s.PF = max_pf(s.V, s.CPL); s.pipe = kPipeGroups;
     }
+    s.chain_block = s.block;
+    if (s.CPL >= 8 && s.V == 4 && G >= 8) {
+        // wide rows on eight or more workgroups: the kernel with an exchange wavefront and a two-level exchange
+        s.split = 1;
+        s.split_ch = s.CPL == 8 ? 1 : 2;
+        s.G = G & ~7;
+        s.chain_block = glm_split_block();
+    }
     s.reduce_mode = ((int64_t)G * p <= 4096) ? kReduceRedundant : kReduceSliced;
     const int64_t th_len = std::max<int64_t>((p + 63) & ~int64_t(63), (int64_t)s.V * s.L * s.CPL);
     s.lds_bytes = (size_t)(th_len + (int64_t)(s.block / 64) * p + s.block + 64) * sizeof(float);
     *out = s;
     return true;
-}
-
-// The kernel of the persistent chain: wide rows over several workgroups have one of their own.
-static KernelFn pick_chain_kernel(const GlmLaunchShape& s)
-{
-    if (s.pipe == kPipeWide && s.G > 1 && s.V == 4 && s.L == 64 && s.block == kWideBlock) {
-        if (s.CPL == 8) return s.with_optimizer ? glm_wide_kernel<8, true> : glm_wide_kernel<8, false>;
-        if (s.CPL == 16) return s.with_optimizer ? glm_wide_kernel<16, true> : glm_wide_kernel<16, false>;
-    }
-    return pick_kernel(s);
 }
 
 hipError_t glm_prepare(GlmLaunchShape* s)
@@ -1025,24 +634,31 @@ hipError_t glm_prepare(GlmLaunchShape* s)
     // one workgroup per compute unit at most: the barrier cost grows with the number of arrivals
     if (s->G > prop.multiProcessorCount) s->G = prop.multiProcessorCount;
     if (s->G > s->max_G) s->G = s->max_G;
-    // the persistent chain may run another kernel for this shape: same shared memory, same residency test
-    KernelFn chain = pick_chain_kernel(*s);
-    if (chain != fn) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(chain), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)s->lds_bytes);
+    if (s->split) {
+        int cap = 0;
+        e = glm_split_prepare(s->split_ch, s->with_optimizer != 0, &cap);
         if (e != hipSuccess) return e;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(chain), s->block, s->lds_bytes);
-        if (e != hipSuccess) return e;
-        if (per_cu < 1) return hipErrorLaunchOutOfResources;
-        s->max_G = std::min(s->max_G, per_cu * prop.multiProcessorCount);
-        if (s->G > s->max_G) s->G = s->max_G;
+        cap = std::min(cap, prop.multiProcessorCount) & ~7;
+        if (cap >= 8) {
+            s->max_G = std::min(s->max_G, cap);
+            s->G = std::min(s->G, cap) & ~7;
+            return hipSuccess;
+        }
+        s->split = 0;                                // not even eight fit: the kernel below takes over
+        s->chain_block = s->block;
     }
     return hipSuccess;
 }
 
 hipError_t glm_launch_chain(const GlmLaunchShape& s, const GlmArgs& args, hipStream_t stream)
 {
-    KernelFn fn = pick_chain_kernel(s);
+    if (s.split) {
+        if (s.G < 8 || s.G > s.max_G) return hipErrorInvalidValue;
+        GlmArgs a = args;
+        a.single_step = -1;
+        return glm_split_launch(s.split_ch, s.with_optimizer != 0, s.G, a, stream);
+    }
+    KernelFn fn = pick_kernel(s);
     if (!fn || s.G < 1 || s.G > s.max_G) return hipErrorInvalidValue;
     GlmArgs a = args;
     a.single_step = -1;

@@ -61,7 +61,7 @@ def test_cfg4_first_four_full_buffers_theta_after_every_buffer():
     w = wl.CONFIGS["cfg4"]
     runs = w.R * w.K if SLOW else 4
     errs, st = parity_after_every_buffer(w, runs, report=_report("cfg4"))
-    assert st.steps == runs * 62 and st.n_workgroups == 256 and st.threads_per_group == 512
+    assert st.steps == runs * 62 and st.n_workgroups == 256 and st.threads_per_group == 704
     assert st.h2d_bytes == runs * w.N0 * (w.p + 1) * 4
     assert max(e[0] for e in errs) <= TOL_F32 and max(e[1] for e in errs) <= TOL_F32
 
@@ -94,7 +94,7 @@ def test_cfg4_shape_short_buffer():
     X, y = wl.dataset(w)
     want = oracle_run(w, X, y)
     got, st = gpu_run(w, X, y, resident=True)
-    assert st.steps == 2 * 4 and st.n_workgroups == 256 and st.threads_per_group == 512
+    assert st.steps == 2 * 4 and st.n_workgroups == 256 and st.threads_per_group == 704
     assert rel_l2(got, want) <= TOL_F32
 
 

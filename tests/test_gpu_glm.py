@@ -111,30 +111,40 @@ def test_workgroup_counts_and_chain_modes(G, chain):
     assert rel_l2(got, want) <= TOL
 
 
+def _wide_threads(n_workgroups, chain):
+    """Threads per workgroup for rows of more than 1024 floats: eight or more workgroups in the persistent chain run the
+    kernel with eight row wavefronts and an exchange wavefront, everything else the 512-thread kernels."""
+    return 704 if chain == 1 and n_workgroups >= 8 else 512
+
+
 def test_wide_rows_grids_and_chain_modes():
-    """p = 4096 and p = 2048 run the whole-workgroup-per-row kernel: single workgroup, sliced reduction on small
-    and full grids, and the step-per-launch mode."""
+    """p = 4096, 2048 and 1540: a single workgroup, a few workgroups (sliced reduction), eight and more workgroups (the
+    kernel with an exchange wavefront and the two-level exchange) up to the full grid, and the step-per-launch mode."""
     for p, alpha in ((4096, 1e-4), (2048, 2e-4), (1540, 2e-4)):
         w = _case(wl.LINEAR, 6000, p, 3000, 1024, T=1, R=1, alpha=alpha, x_cov="identity")
         X, y = wl.dataset(w)
         want = oracle_run(w, X, y)
-        for G, chain in ((1, 1), (3, 1), (48, 1), (256, 1), (64, 2)):
+        for G, chain in ((1, 1), (3, 1), (8, 1), (48, 1), (256, 1), (64, 2)):
             got, st = gpu_run(w, X, y, n_workgroups=G, chain=chain)
-            assert st.n_workgroups == G and st.threads_per_group == 512
+            assert st.n_workgroups == G and st.threads_per_group == _wide_threads(G, chain)
             assert rel_l2(got, want) <= TOL, (p, G, chain)
 
 
 @pytest.mark.parametrize("model,p,n,G", [(wl.LINEAR, 4096, 1000, 5), (wl.LOGISTIC, 4096, 700, 24), (wl.LINEAR, 2052, 900, 40),
-                                         (wl.LOGISTIC, 1028, 512, 0), (wl.LINEAR, 3000, 333, 2)])
-def test_wide_rows_two_rows_in_flight(model, p, n, G):
-    """Wide rows over several workgroups: the kernel that keeps two rows per wavefront in flight.  Odd and even numbers
-    of row groups per step (a step then ends on either register set), one group per step, a ragged last batch, several
-    passes and buffers, columns that do not fill the last chunk."""
+                                         (wl.LOGISTIC, 1028, 512, 0), (wl.LINEAR, 3000, 333, 2), (wl.LINEAR, 4096, 100, 16),
+                                         (wl.LOGISTIC, 2048, 2500, 256), (wl.LINEAR, 4092, 1111, 30)])
+def test_wide_rows_rows_in_flight_across_steps(model, p, n, G):
+    """Wide rows over several workgroups, both kernels (fewer than eight workgroups: two rows per wavefront in flight;
+    eight or more: rows split over the wavefronts of a workgroup, groups of rows in flight, exchange wavefront).
+    Steps that end on every slot of the ring, one group per step, workgroups without a row in a step, a ragged
+    last batch, several passes and buffers, columns that do not fill the last chunk, a requested workgroup count that
+    is not a multiple of eight (rounded down)."""
     w = _case(model, 5000, p, 2500, n, T=2, R=2, alpha=(0.2 / p) if model == wl.LINEAR else 0.05, x_cov="identity")
     X, y = wl.dataset(w)
     want = oracle_run(w, X, y)
     got, st = gpu_run(w, X, y, n_workgroups=G, chain=1)
-    assert st.threads_per_group == 512 and st.n_workgroups > 1
+    assert st.threads_per_group == _wide_threads(st.n_workgroups, 1) and st.n_workgroups > 1
+    assert G < 8 or st.n_workgroups % 8 == 0
     assert rel_l2(got, want) <= TOL, (p, n, st.n_workgroups)
     again, _ = gpu_run(w, X, y, n_workgroups=G, chain=1, resident=True)
     assert np.array_equal(got, again)
@@ -148,7 +158,7 @@ def test_wide_rows_one_step_per_launch_and_one_row_per_wavefront():
         X, y = wl.dataset(w)
         want = oracle_run(w, X, y)
         got, st = gpu_run(w, X, y, n_workgroups=G, chain=1)
-        assert st.threads_per_group == 512 and st.n_workgroups == G
+        assert st.threads_per_group == _wide_threads(G, 1) and st.n_workgroups == G
         assert rel_l2(got, want) <= TOL, (p, N0, n, T, G)
 
 
