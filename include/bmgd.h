@@ -48,6 +48,14 @@
  *     stream, the library's chain stream) and reuses them.
  *   - If no usable GPU is present every call that needs one fails with
  *     BMGD_EHIP; there is no CPU fallback.
+ *   - A run that fails after part of its work has been enqueued, a device-side wait that exceeds
+ *     barrier_timeout_us (the persistent kernels need all their workgroups resident at once: work of
+ *     other streams that holds compute units for longer than the limit makes a run give up; it exits by
+ *     itself and the next blocking call returns BMGD_EHIP) and a row subset with an index outside its
+ *     buffer leave theta undefined.  From then on every run call returns BMGD_ESTATE until theta has been
+ *     set again with bmgd_set_theta() (bmgd_set_position() and bmgd_reset_optimizer() restore the rest of
+ *     a checkpoint); nothing is retried automatically, because runs enqueued behind the failed one have
+ *     already used its result.
  */
 #ifndef BMGD_H
 #define BMGD_H
@@ -96,12 +104,17 @@ enum {
     BMGD_CHAIN_AUTO = 0,
     BMGD_CHAIN_PERSISTENT = 1,   /* one persistent kernel per buffer; workgroups exchange sums once per step */
     BMGD_CHAIN_LAUNCH = 2,       /* kernel launches per step, in stream order */
-    BMGD_CHAIN_GRAM = 3          /* least squares with p <= 128 only: the update in the form of eq. (3.1),
+    BMGD_CHAIN_GRAM = 3,         /* least squares with p <= 128 only: the update in the form of eq. (3.1),
                                     theta <- (I - alpha Sxx_m) theta + alpha Sxy_m.  The moment matrices of every
                                     mini-batch of a pass are formed first, in parallel over the buffer (each row
                                     read once), and the sequential chain then runs inside one workgroup at p^2
                                     multiply-adds per step.  Same result as the row form up to the order of
                                     summation.  BMGD_CHAIN_AUTO picks it when it applies and batch_n >= 2 p. */
+    BMGD_CHAIN_GRAPH = 4         /* softmax only (its BMGD_CHAIN_AUTO): the launches of one pass over one buffer - the transpose of
+                                    its mini-batches, then logits, residual and gradient + update per mini-batch - are captured
+                                    once into a HIP graph per (buffer address, rows, partition slot) and replayed; learning
+                                    rate and update counts are read from device memory, so a replay needs no new capture.
+                                    BMGD_CHAIN_LAUNCH issues the same launches one by one. */
 };
 
 /* update rule fed with the mini-batch gradient g of eq. (2.1) (Section 4.3 combines the buffering idea with NAG and
@@ -192,7 +205,8 @@ size_t bmgd_workspace_bytes(const bmgd_config* cfg);
  * copy of `rows` rows into the slot that is not being computed on.
  *   host_x  host, row-major [rows][p], fp32 or bf16 per x_dtype.  Pinned memory is needed for the copy
  *           to overlap with compute.
- *   host_y  host, [rows]: fp32 responses (0/1 for logistic) or int32 class ids in [0, C) for softmax.
+ *   host_y  host, [rows]: fp32 responses (0/1 for logistic) or int32 class ids for softmax.  Class ids must lie in
+ *           [0, C): they are not checked, and an id outside that range makes its row count as belonging to no class.
  * The memory must stay valid and unchanged until the copy has completed (bmgd_sync, or a
  * synchronisation of copy_stream by the caller).  The copy waits, on the device, for the run that last
  * read the target slot.  At most one loaded-but-not-run buffer may exist: a second load without a run in
@@ -309,7 +323,8 @@ int bmgd_run_device_buffer(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, 
 int bmgd_get_theta(bmgd_ctx* ctx, float* host_out, int64_t len);
 
 /* Wait for all enqueued work, then overwrite theta (the initial value of Algorithm 1, or a checkpoint).  The state
- * of the optimizer is left as it is; bmgd_reset_optimizer() zeroes it. */
+ * of the optimizer is left as it is; bmgd_reset_optimizer() zeroes it.  Also the way back after a failed or
+ * abandoned run (see the general rules): the failure, if not reported yet, is not reported by this call. */
 int bmgd_set_theta(bmgd_ctx* ctx, const float* host_in, int64_t len);
 
 /* Wait for all enqueued work, then set the optimizer's state (v; m, s and the update count k) back to zero. */

@@ -8,7 +8,9 @@
 #include <string.h>
 
 #include <algorithm>
+#include <map>
 #include <new>
+#include <tuple>
 #include <string>
 #include <utility>
 #include <vector>
@@ -31,7 +33,7 @@ constexpr int kMaxGroups = 256;                    // upper bound used to size t
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, wbt, u, rt, xt, gram[2], gram_perm, gram_cache, gram_cache_set, opt_m, opt_s, opt_len, eval, swa, total;
+    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, sm_state, wbt, u, rt, xt, gram[2], gram_perm, gram_cache, gram_cache_set, opt_m, opt_s, opt_len, eval, swa, total;
 };
 
 struct Slot {
@@ -73,6 +75,11 @@ struct bmgd_ctx {
     unsigned long long* ll_part = nullptr;
     unsigned long long* ll_theta = nullptr;
     unsigned* sync = nullptr;
+    SoftmaxState* sm_state = nullptr;              // softmax: learning rate and update counts of the pass being enqueued (device)
+    // softmax, BMGD_CHAIN_GRAPH: the launches of one pass over one buffer, captured once per (buffer, rows, partition
+    // slot) on a stream of the library's own and replayed on the caller's stream
+    std::map<std::tuple<const void*, const void*, const int32_t*, int64_t>, hipGraphExec_t> pass_graphs;
+    hipStream_t capture_stream = nullptr;
     void* wbt = nullptr;                           // softmax: bf16 copy of W, transposed
     float* u = nullptr;                            // softmax: logits scratch
     void* rt = nullptr;                            // softmax: residual scratch
@@ -127,6 +134,7 @@ struct bmgd_ctx {
     RunRecord pending_copy;                        // copy events of the buffer that is loaded but not run
     hipStream_t last_copy = nullptr, last_compute = nullptr;
     bool used_copy = false, used_compute = false;
+    bool poisoned = false;                         // a run failed or was abandoned: theta is not valid until it is set again
     std::string err;
 };
 
@@ -152,8 +160,11 @@ bool valid_config(const bmgd_config& c, std::string* why)
     if (c.reshuffle != BMGD_RESHUFFLE_PER_PASS && c.reshuffle != BMGD_RESHUFFLE_FIXED) return bad("unknown reshuffle mode");
     if (c.n_buffers < 0) return bad("n_buffers must be non-negative");
     if (c.chain != BMGD_CHAIN_AUTO && c.chain != BMGD_CHAIN_PERSISTENT && c.chain != BMGD_CHAIN_LAUNCH &&
-        c.chain != BMGD_CHAIN_GRAM)
+        c.chain != BMGD_CHAIN_GRAM && c.chain != BMGD_CHAIN_GRAPH)
         return bad("unknown chain mode");
+    if (c.chain == BMGD_CHAIN_GRAPH && c.model != BMGD_SOFTMAX) return bad("BMGD_CHAIN_GRAPH is the softmax model's mode");
+    if (c.model == BMGD_SOFTMAX && (c.chain == BMGD_CHAIN_PERSISTENT || c.chain == BMGD_CHAIN_GRAM))
+        return bad("softmax runs with BMGD_CHAIN_AUTO, BMGD_CHAIN_GRAPH or BMGD_CHAIN_LAUNCH");
     if (c.chain == BMGD_CHAIN_GRAM && (c.model != BMGD_LINEAR || c.p > kGramMaxP))
         return bad("BMGD_CHAIN_GRAM needs the linear model and p <= 128");
     if (c.n_workgroups < 0 || c.n_workgroups > kMaxGroups) return bad("n_workgroups must be in [0, 256]");
@@ -206,6 +217,7 @@ Layout make_layout(const bmgd_config& c)
         l.theta = off;   off += align_up((size_t)c.p * d.c_pad * 4);             // fp32 master, [p][c_pad]
         l.partial = l.ll_part = l.ll_theta = off;
         l.sync = off;    off += align_up(64);
+        l.sm_state = off; off += align_up(sizeof(SoftmaxState));
         l.wbt = off;     off += align_up((size_t)d.c_pad * d.p_pad * 2);
         l.u = off;       off += align_up((size_t)8 * d.m_pad * d.c_pad * 4);
         l.rt = off;      off += align_up((size_t)d.c_pad * d.n_pad * 2);
@@ -217,7 +229,7 @@ Layout make_layout(const bmgd_config& c)
         l.ll_part = off; off += align_up((size_t)2 * kMaxGroups * pp * 8);
         l.ll_theta = off; off += align_up((size_t)2 * kThetaCopies * pp * 8);
         l.sync = off;    off += align_up(64);
-        l.wbt = l.u = l.rt = l.xt = off;
+        l.sm_state = l.wbt = l.u = l.rt = l.xt = off;
     }
     l.gram[0] = l.gram[1] = l.gram_perm = off;
     if (resolve_chain(c) == BMGD_CHAIN_GRAM) {
@@ -255,7 +267,7 @@ Layout make_layout(const bmgd_config& c)
 
 int resolve_chain(const bmgd_config& c)
 {
-    if (c.model == BMGD_SOFTMAX) return BMGD_CHAIN_LAUNCH;
+    if (c.model == BMGD_SOFTMAX) return c.chain == BMGD_CHAIN_LAUNCH ? BMGD_CHAIN_LAUNCH : BMGD_CHAIN_GRAPH;
     if (c.chain != BMGD_CHAIN_AUTO) return c.chain;
     return gram_eligible(c.model, c.p, c.batch_n) ? BMGD_CHAIN_GRAM : BMGD_CHAIN_PERSISTENT;
 }
@@ -370,9 +382,10 @@ int drain(bmgd_ctx* ctx)
     HIP_TRY(ctx, hipMemcpy(flag, ctx->sync + 1, sizeof flag, hipMemcpyDeviceToHost));
     if (flag[0] != 0 || flag[1] != 0) {
         HIP_TRY(ctx, hipMemset(ctx->sync, 0, 64));
+        ctx->poisoned = true;
         if (flag[0] != 0)
-            return fail(ctx, BMGD_EHIP, "a device-side wait exceeded barrier_timeout_us; the run was abandoned and theta is not valid");
-        return fail(ctx, BMGD_EINVAL, "a row subset held an index outside its buffer (row 0 was used in its place); theta is not valid");
+            return fail(ctx, BMGD_EHIP, "a device-side wait exceeded barrier_timeout_us; the run was abandoned and theta is not valid (set it again with bmgd_set_theta before the next run)");
+        return fail(ctx, BMGD_EINVAL, "a row subset held an index outside its buffer (row 0 was used in its place); theta is not valid (set it again with bmgd_set_theta before the next run)");
     }
     return BMGD_OK;
 }
@@ -417,6 +430,10 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
     const uint32_t b = (uint32_t)(fixed && c.n_buffers > 0 ? ctx->buffer_counter % c.n_buffers : ctx->buffer_counter);
     const long long ticks = (c.barrier_timeout_us > 0 ? c.barrier_timeout_us : 2000000) * 100LL;
     const int lr_len = (int)ctx->lr_tab_host.size();
+    // checked before anything is enqueued: step indices inside one launch stay below 2^23
+    if (c.model != BMGD_SOFTMAX && ctx->chain != BMGD_CHAIN_GRAM &&
+        (int64_t)std::min(kMaxPassesPerLaunch, count) * M >= (int64_t(1) << 23))
+        return fail(ctx, BMGD_EINVAL, "passes per launch * batches per pass must stay below 2^23; use a larger batch_n");
 
     for (int t0 = first; t0 < first + count; t0 += kMaxPassesPerLaunch) {
         const int np = std::min(kMaxPassesPerLaunch, first + count - t0);
@@ -493,9 +510,10 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
             HIP_TRY(ctx, hipEventRecord(ev0, stream));
             const SoftmaxDims d = softmax_dims(c.p, n, c.n_classes);
             const SoftmaxDims dmax = softmax_dims(c.p, c.batch_n, c.n_classes);
-            for (int i = 0; i < np; ++i) {
-                const int32_t* pm = ctx->perm + (fixed ? 0 : (size_t)i * rows);
-                HIP_TRY(ctx, softmax_permute_transpose(x, pm, ctx->xt, (int)rows, (int)c.p, (int)n, d, stream));
+            // the launches of one pass (transpose of its mini-batches, then logits / residual / gradient + update per
+            // mini-batch), onto `to`
+            auto issue_pass = [&](const int32_t* pm, hipStream_t to) -> int {
+                HIP_TRY(ctx, softmax_permute_transpose(x, pm, ctx->xt, (int)rows, (int)c.p, (int)n, d, to));
                 for (int64_t m = 0; m < M; ++m) {
                     SoftmaxStep st{};
                     st.X = x;
@@ -509,19 +527,55 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
                     st.nb = (int)std::min<int64_t>(n, rows - m * n);
                     st.p = (int)c.p;
                     st.C = c.n_classes;
-                    st.alpha = rate_of(ctx, (int64_t)i * M + m);
-                    st.opt = opt_args(ctx, (int64_t)i * M + m);
+                    st.opt = opt_args(ctx, 0);
+                    st.state = ctx->sm_state;
+                    st.u = (int)m;
+                    st.lr_tab = lr_len ? ctx->lr_tab_dev : nullptr;
+                    st.lr_len = lr_len;
                     SoftmaxDims ds = d;
                     ds.c_pad = dmax.c_pad;           // W and WbT keep the strides fixed at creation
                     ds.p_pad = dmax.p_pad;
-                    HIP_TRY(ctx, softmax_step(st, ds, stream));
+                    HIP_TRY(ctx, softmax_step(st, ds, to));
                 }
+                return BMGD_OK;
+            };
+            for (int i = 0; i < np; ++i) {
+                const int32_t* pm = ctx->perm + (fixed ? 0 : (size_t)i * rows);
+                // what differs between two passes with the same launches: read by the kernels from device memory
+                HIP_TRY(ctx, softmax_set_state(ctx->sm_state, (float)c.lr, (int)std::min<int64_t>(ctx->lr_pos, 0x7FFFFFF0),
+                                               (int)std::min<int64_t>(ctx->opt_k, 0x7FFFFFF0), stream));
+                if (ctx->chain == BMGD_CHAIN_GRAPH) {
+                    const auto key = std::make_tuple(x, y, pm, rows);
+                    auto it = ctx->pass_graphs.find(key);
+                    if (it == ctx->pass_graphs.end()) {
+                        if (ctx->pass_graphs.size() >= 64) {   // callers that keep bringing new buffers: start over
+                            HIP_TRY(ctx, hipStreamSynchronize(stream));
+                            for (auto& kv : ctx->pass_graphs) (void)hipGraphExecDestroy(kv.second);
+                            ctx->pass_graphs.clear();
+                        }
+                        hipGraph_t graph = nullptr;
+                        HIP_TRY(ctx, hipStreamBeginCapture(ctx->capture_stream, hipStreamCaptureModeThreadLocal));
+                        const int rc = issue_pass(pm, ctx->capture_stream);
+                        const hipError_t ce = hipStreamEndCapture(ctx->capture_stream, &graph);
+                        if (rc != BMGD_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+                        if (ce != hipSuccess) return hip_fail(ctx, ce, "hipStreamEndCapture");
+                        hipGraphExec_t exec = nullptr;
+                        const hipError_t ie = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+                        (void)hipGraphDestroy(graph);
+                        if (ie != hipSuccess) return hip_fail(ctx, ie, "hipGraphInstantiate");
+                        it = ctx->pass_graphs.emplace(key, exec).first;
+                    }
+                    HIP_TRY(ctx, hipGraphLaunch(it->second, stream));
+                } else {
+                    const int rc = issue_pass(pm, stream);
+                    if (rc != BMGD_OK) return rc;
+                }
+                ctx->lr_pos += M;
+                ctx->opt_k += M;
             }
             HIP_TRY(ctx, hipEventRecord(ev1, stream));
             ctx->open_chain.emplace_back(ev0, ev1);
             if (chunk_end) *chunk_end = ev1;
-            ctx->lr_pos += (int64_t)np * M;
-            ctx->opt_k += (int64_t)np * M;
             continue;
         }
         GlmArgs a{};
@@ -547,8 +601,6 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
         a.lr_base = (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0));
         a.lr_len = lr_len;
         a.opt = opt_args(ctx, 0);
-        if ((int64_t)np * M >= (int64_t(1) << 23))
-            return fail(ctx, BMGD_EINVAL, "passes per launch * batches per pass must stay below 2^23; use a larger batch_n");
         HIP_TRY(ctx, hipEventRecord(ev0, stream));
         if (ctx->chain == BMGD_CHAIN_PERSISTENT) {
             const int64_t nsteps = (int64_t)np * M;
@@ -604,6 +656,23 @@ int64_t rows_of_run(bmgd_ctx* ctx, int64_t buffer_rows)
     return ctx->subset_count;
 }
 
+// A run call failed after it may have enqueued part of its work: the events it took go back to the pool, and theta
+// counts as not valid (the kernels already enqueued have updated it for part of the run) until it is set again.
+int abandon_run(bmgd_ctx* ctx, RunRecord& rec, int rc)
+{
+    give_event(ctx, rec.start);
+    if (rec.owns_end) give_event(ctx, rec.end);
+    rec.start = rec.end = nullptr;
+    ctx->poisoned = true;
+    return rc;
+}
+
+int refuse_if_poisoned(bmgd_ctx* ctx)
+{
+    if (!ctx->poisoned) return BMGD_OK;
+    return fail(ctx, BMGD_ESTATE, "an earlier run failed or was abandoned and theta is not valid: call bmgd_set_theta first");
+}
+
 // Enqueue the T passes of Algorithm 1 over (x, y, rows).
 int enqueue_compute(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hipStream_t stream, hipEvent_t* end_event)
 {
@@ -621,6 +690,8 @@ void destroy_ctx(bmgd_ctx* ctx)
     if (ctx->chain_stream) (void)hipStreamSynchronize(ctx->chain_stream);
     settle_records(ctx, ctx->open_records.size());
     if (ctx->chain_stream) (void)hipStreamDestroy(ctx->chain_stream);
+    for (auto& kv : ctx->pass_graphs) (void)hipGraphExecDestroy(kv.second);
+    if (ctx->capture_stream) (void)hipStreamDestroy(ctx->capture_stream);
     give_event(ctx, ctx->pending_copy.copy_start);
     give_event(ctx, ctx->pending_copy.copy_end);
     for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
@@ -723,6 +794,7 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->ll_part = reinterpret_cast<unsigned long long*>(base + ctx->lay.ll_part);
     ctx->ll_theta = reinterpret_cast<unsigned long long*>(base + ctx->lay.ll_theta);
     ctx->sync = reinterpret_cast<unsigned*>(base + ctx->lay.sync);
+    ctx->sm_state = reinterpret_cast<SoftmaxState*>(base + ctx->lay.sm_state);
     ctx->wbt = base + ctx->lay.wbt;
     ctx->u = reinterpret_cast<float*>(base + ctx->lay.u);
     ctx->rt = base + ctx->lay.rt;
@@ -755,7 +827,8 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
 
     if (cfg->model == BMGD_SOFTMAX) {
         CREATE_TRY(softmax_prepare(softmax_dims(cfg->p, cfg->batch_n, cfg->n_classes)));
-        ctx->chain = BMGD_CHAIN_LAUNCH;              // three launches per mini-batch update, in stream order
+        ctx->chain = resolve_chain(ctx->cfg);        // three launches per mini-batch update, replayed from a graph or issued one by one
+        if (ctx->chain == BMGD_CHAIN_GRAPH) CREATE_TRY(hipStreamCreateWithFlags(&ctx->capture_stream, hipStreamNonBlocking));
     } else {
         char msg[160];
         if (!glm_plan(cfg->p, cfg->batch_n, cfg->n_workgroups, ctx->num_cus, &ctx->shape, msg, sizeof msg)) {
@@ -829,6 +902,7 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
 {
     if (!ctx) return BMGD_EINVAL;
     if (ctx->pending < 0) return fail(ctx, BMGD_ESTATE, "no buffer is loaded");
+    if (refuse_if_poisoned(ctx) != BMGD_OK) return BMGD_ESTATE;
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     hipStream_t s = static_cast<hipStream_t>(compute_stream);
     Slot& slot = ctx->slots[ctx->pending];
@@ -845,7 +919,7 @@ BMGD_API int bmgd_run_buffer(bmgd_ctx* ctx, void* compute_stream)
     ctx->subset = nullptr;                                        // a subset holds for one run
     ctx->last_compute = s;
     ctx->used_compute = true;
-    if (rc != BMGD_OK) return rc;
+    if (rc != BMGD_OK) return abandon_run(ctx, rec, rc);
     if (last) { give_event(ctx, rec.end); rec.end = last; rec.owns_end = false; }
     else HIP_TRY(ctx, hipEventRecord(rec.end, s));
     HIP_TRY(ctx, hipEventRecord(slot.compute_done, s));           // every kernel that reads the slot runs on s
@@ -867,6 +941,7 @@ static int run_adaptive(bmgd_ctx* ctx, hipStream_t s, hipStream_t cs, const void
     if (passes_done) *passes_done = 0;
     if (next_rows_out) *next_rows_out = 0;
     if (ctx->pending < 0) return fail(ctx, BMGD_ESTATE, "no buffer is loaded");
+    if (refuse_if_poisoned(ctx) != BMGD_OK) return BMGD_ESTATE;
     if (min_passes < 1 || max_passes < min_passes || max_passes > (1 << 20))
         return fail(ctx, BMGD_EINVAL, "need 1 <= min_passes <= max_passes <= 2^20");
     HIP_TRY(ctx, hipSetDevice(ctx->device));
@@ -930,7 +1005,19 @@ static int run_adaptive(bmgd_ctx* ctx, hipStream_t s, hipStream_t cs, const void
         if (in_flight[0]) HIP_TRY(ctx, hipEventSynchronize(in_flight[0]));
         hipEvent_t chunk = nullptr;
         const int rc = enqueue_passes(ctx, slot.x, slot.y, run_rows, s, passes, 1, &last, &chunk);
-        if (rc != BMGD_OK) return rc;
+        if (rc != BMGD_OK) {
+            if (next_slot >= 0) {
+                // the copy of the next buffer has been started: that buffer is the loaded one now, and the events of
+                // this buffer's copy (which every kernel enqueued so far already waits for) go back to the pool
+                give_event(ctx, rec.copy_start); give_event(ctx, rec.copy_end);
+                ctx->pending_copy = next_rec;
+                ctx->pending = next_slot;
+            } else {
+                ctx->pending_copy = rec;                 // still the loaded buffer, with its copy events
+                ctx->pending_copy.start = ctx->pending_copy.end = nullptr;
+            }
+            return abandon_run(ctx, rec, rc);
+        }
         in_flight[0] = in_flight[1];
         in_flight[1] = chunk;
         passes += 1;
@@ -981,6 +1068,7 @@ BMGD_API int bmgd_run_buffer_adaptive_reader(bmgd_ctx* ctx, void* compute_stream
 // are cached: then no row is read).
 static int run_resident(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int64_t rows, hipStream_t s)
 {
+    if (refuse_if_poisoned(ctx) != BMGD_OK) return BMGD_ESTATE;
     HIP_TRY(ctx, hipSetDevice(ctx->device));
     const int64_t run_rows = rows_of_run(ctx, rows);
     if (run_rows == 0) return BMGD_EINVAL;
@@ -994,7 +1082,7 @@ static int run_resident(bmgd_ctx* ctx, const void* dev_x, const void* dev_y, int
     ctx->subset = nullptr;
     ctx->last_compute = s;
     ctx->used_compute = true;
-    if (rc != BMGD_OK) return rc;
+    if (rc != BMGD_OK) return abandon_run(ctx, rec, rc);
     if (last) { give_event(ctx, rec.end); rec.end = last; rec.owns_end = false; }
     else HIP_TRY(ctx, hipEventRecord(rec.end, s));
     rec.n_chain = (int)(ctx->open_chain.size() - chain0);
@@ -1100,8 +1188,9 @@ BMGD_API int bmgd_set_theta(bmgd_ctx* ctx, const float* host_in, int64_t len)
     if (!ctx) return BMGD_EINVAL;
     if (!host_in) return fail(ctx, BMGD_EINVAL, "host_in must not be NULL");
     if (len != ctx->theta_len) return fail(ctx, BMGD_EINVAL, "len must equal p (p * n_classes for softmax)");
-    const int rc = drain(ctx);
-    if (rc != BMGD_OK) return rc;
+    const int rc = drain(ctx);                           // (an abandoned run found only now is what this call is the remedy for)
+    if (rc != BMGD_OK && !ctx->poisoned) return rc;
+    ctx->poisoned = false;
     if (ctx->cfg.model == BMGD_SOFTMAX) {
         const SoftmaxDims d = softmax_dims(ctx->cfg.p, ctx->cfg.batch_n, ctx->cfg.n_classes);
         const size_t C = (size_t)ctx->cfg.n_classes;
@@ -1195,6 +1284,9 @@ BMGD_API int bmgd_set_lr_schedule(bmgd_ctx* ctx, const float* host_alphas, int64
             return fail(ctx, BMGD_EINVAL, "every learning rate must be finite and positive");
     const int rc = drain(ctx);
     if (rc != BMGD_OK) return rc;
+    // captured passes hold the table's address and length among their kernels' arguments: captured again when next used
+    for (auto& kv : ctx->pass_graphs) (void)hipGraphExecDestroy(kv.second);
+    ctx->pass_graphs.clear();
     if (ctx->lr_tab_dev) { HIP_TRY(ctx, hipFree(ctx->lr_tab_dev)); ctx->lr_tab_dev = nullptr; }
     ctx->lr_tab_host.clear();
     ctx->lr_pos = 0;

@@ -178,18 +178,29 @@ struct SoftmaxDims {
     int k_per_split;
 };
 
+// What changes from pass to pass without changing the sequence of launches: read by the update kernels from device
+// memory, written in stream order before each pass.
+struct SoftmaxState {
+    float alpha;        // learning rate when no per-update table is set
+    int lr_pos;         // updates enqueued since the table was set, before this pass
+    int opt_k;          // updates made before this pass (Adam's bias corrections)
+};
+
 struct SoftmaxStep {
     const void* X;          // slot, bf16 [rows][p]
     const int32_t* y;       // class ids [rows]
     const int32_t* idx;     // the mini-batch: nb entries of the partition
     const void* XT;         // bf16 [p][n_pad]: this mini-batch transposed
     float* W;               // fp32 master [p][c_pad]
-    OptArgs opt;            // state arrays laid out like W; k_base = updates made before this one
+    OptArgs opt;            // state arrays laid out like W (k_base unused: the count comes from `state`)
+    const SoftmaxState* state;
+    int u;                  // number of this update within its pass
+    const float* lr_tab;    // optional learning rate per update (device), lr_len entries
+    int lr_len;
     void* WbT;              // bf16 copy, transposed [c_pad][p_pad]
     float* U;               // logits scratch [splits][m_pad][c_pad]
     void* Rt;               // residual scratch, bf16 [c_pad][n_pad]
     int nb, p, C;
-    float alpha;
 };
 
 SoftmaxDims softmax_dims(int64_t p, int64_t n, int64_t C);
@@ -199,6 +210,8 @@ hipError_t softmax_permute_transpose(const void* X, const int32_t* perm, void* X
                                      const SoftmaxDims& d, hipStream_t stream);
 // One mini-batch update: logits, residual, gradient + update (three launches in stream order).
 hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t stream);
+// *state <- (alpha, lr_pos, opt_k), in stream order.
+hipError_t softmax_set_state(SoftmaxState* state, float alpha, int lr_pos, int opt_k, hipStream_t stream);
 // Evaluation: cross-entropy summed over `nb` rows X[row0 .. row0 + nb) (contiguous, nb <= the batch size the context
 // was created with) at the bf16 copy of W: partial[b] for b < ceil(nb / 8) workgroups.
 hipError_t softmax_launch_loss(const void* X, const int32_t* y, int nb, int p, int C, const void* WbT, float* U,

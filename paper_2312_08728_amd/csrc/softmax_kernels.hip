@@ -90,9 +90,15 @@ struct GemmArgs {
     float* W;                   // [p][ldw] fp32 master
     unsigned short* WbT;        // [ldw][ldwt] bf16 copy, transposed
     int ldw, ldwt;
-    float scale;                // alpha / n_b
-    float alpha, inv_nb;
-    OptArgs opt;                // state arrays [p][ldw] like W; plain steps if kind == kOptSgd
+    float inv_nb;               // 1 / n_b
+    // The learning rate and the update count come from device memory, so that a captured sequence of launches can be
+    // replayed: update number u (within the pass: a constant of the launch) uses
+    // lr_tab[min(state->lr_pos + u, lr_len - 1)], or state->alpha without a table, and Adam's count state->opt_k + u + 1.
+    const SoftmaxState* state;
+    int u;
+    const float* lr_tab;
+    int lr_len;
+    OptArgs opt;                // state arrays [p][ldw] like W; plain steps if kind == kOptSgd (k_base unused)
     int tiles_m, tiles_n, splits;   // work items = splits * tiles_m * tiles_n, dealt to XCDs in contiguous runs
 };
 
@@ -222,8 +228,10 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
                     if (r < g.m_pad && c < g.ldu) U[(size_t)r * g.ldu + c] = acc[i][j][v];
                 }
     } else {
+        const float alpha = g.lr_tab ? g.lr_tab[min(g.state->lr_pos + g.u, g.lr_len - 1)] : g.state->alpha;
+        const float scale = alpha * g.inv_nb;
         float oc1 = 1.f, oc2 = 1.f;
-        if (OPT && g.opt.kind == kOptAdam) opt_corrections(g.opt, g.opt.k_base + 1, oc1, oc2);
+        if (OPT && g.opt.kind == kOptAdam) opt_corrections(g.opt, g.state->opt_k + g.u + 1, oc1, oc2);
         // rows are features, columns are classes: W[r][c] -= scale * acc; bf16 copy goes out transposed.
         // The 32 master weights of a half-quadrant are requested together, from clamped addresses and without a
         // branch, and only then combined and stored (a branch around each load would wait for it on the spot).
@@ -248,12 +256,12 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
                     const bool ok = r < g.M && c < g.ldw;
                     float w = 0.f;
                     if constexpr (!OPT) {
-                        w = ok ? wv[j][v] - g.scale * acc[i][j][v] : 0.f;
+                        w = ok ? wv[j][v] - scale * acc[i][j][v] : 0.f;
                     } else if (ok) {
                         // the state is read here, element by element: this path trades speed for the extra arrays
                         const size_t at = (size_t)r * g.ldw + c;
                         float m = g.opt.m[at], sv = g.opt.kind == kOptAdam ? g.opt.s[at] : 0.f;
-                        w = opt_update(g.opt, wv[j][v], acc[i][j][v] * g.inv_nb, g.alpha, m, sv, oc1, oc2);
+                        w = opt_update(g.opt, wv[j][v], acc[i][j][v] * g.inv_nb, alpha, m, sv, oc1, oc2);
                         g.opt.m[at] = m;
                         if (g.opt.kind == kOptAdam) g.opt.s[at] = sv;
                     }
@@ -435,7 +443,20 @@ __global__ void __launch_bounds__(256) shadow_kernel(const float* __restrict__ W
     }
 }
 
+__global__ void softmax_state_kernel(SoftmaxState* st, float alpha, int lr_pos, int opt_k)
+{
+    st->alpha = alpha;
+    st->lr_pos = lr_pos;
+    st->opt_k = opt_k;
+}
+
 }  // namespace
+
+hipError_t softmax_set_state(SoftmaxState* state, float alpha, int lr_pos, int opt_k, hipStream_t stream)
+{
+    hipLaunchKernelGGL(softmax_state_kernel, dim3(1), dim3(1), 0, stream, state, alpha, lr_pos, opt_k);
+    return hipGetLastError();
+}
 
 SoftmaxDims softmax_dims(int64_t p, int64_t n, int64_t C)
 {
@@ -537,9 +558,11 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
     h.WbT = static_cast<unsigned short*>(s.WbT);
     h.ldw = d.c_pad;
     h.ldwt = d.p_pad;
-    h.scale = s.alpha / (float)s.nb;
-    h.alpha = s.alpha;
     h.inv_nb = 1.f / (float)s.nb;
+    h.state = s.state;
+    h.u = s.u;
+    h.lr_tab = s.lr_tab;
+    h.lr_len = s.lr_len;
     h.opt = s.opt;
     h.tiles_m = d.p_pad / TM;
     h.tiles_n = d.c_pad / TN;

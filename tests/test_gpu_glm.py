@@ -308,6 +308,15 @@ def test_device_side_wait_is_bounded():
     out = np.zeros(w.p, dtype=np.float32)
     assert B.bmgd_get_theta(c.h, out, w.p) == B.BMGD_EHIP
     assert "barrier_timeout_us" in B.bmgd_last_error(c.h)
+    # theta is undefined now: runs are refused until it has been set again, then the context works as before
+    assert B.bmgd_run_device_buffer(c.h, xd, yd, w.N0, None) == B.BMGD_ESTATE
+    assert "bmgd_set_theta" in B.bmgd_last_error(c.h)
+    c.set_theta(np.zeros(w.p, dtype=np.float32))
+    c.set_position(0)
+    assert B.bmgd_run_device_buffer(c.h, xd, yd, w.N0, None) == B.BMGD_OK      # accepted (and gives up again: same limit)
+    assert B.bmgd_sync(c.h) == B.BMGD_EHIP
+    c.set_theta(np.zeros(w.p, dtype=np.float32))                               # the failure was reported: plain success
+    assert np.array_equal(c.get_theta(), np.zeros(w.p, dtype=np.float32))
     c.close()
     got, _ = gpu_run(w, X, y, n_workgroups=64, chain=1)          # default limit: same shape runs to the end
     assert rel_l2(got, oracle_run(w, X, y)) <= TOL

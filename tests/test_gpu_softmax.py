@@ -79,3 +79,41 @@ def test_softmax_learning_rate_per_update():
     got = ctx.get_theta().reshape(w.p, w.C)
     ctx.close()
     assert rel_l2(got, ref.theta) <= TOL
+
+
+@pytest.mark.parametrize("optimizer", [0, 3])
+def test_graph_replays_equal_single_launches(optimizer):
+    """The captured pass (BMGD_CHAIN_GRAPH, the default) against the same launches issued one by one
+    (BMGD_CHAIN_LAUNCH): bit-identical W after every buffer, over several replays of each graph, with blocking calls,
+    a change of the learning rate, a per-update schedule and other device work between the replays; a buffer with
+    fewer rows (other graphs) in the rotation; plain steps and Adam (whose update count comes from device memory)."""
+    import torch
+    import paper_2312_08728_amd as B
+    w = _case(2300, 128, 40, 1000, 128, T=2)                      # buffers of 1000, 1000 and 300 rows
+    X, y = wl.dataset(w)
+    xd, yd = torch.from_numpy(X.view(np.int16)).cuda(), torch.from_numpy(y).cuda()
+    s = torch.cuda.Stream()
+    scratch = torch.zeros(1 << 20, device="cuda")
+    ctxs = [B.Context(w.p, w.N0, w.n, w.alpha, w.T, model=w.model, n_classes=w.C, chain=chain, optimizer=optimizer)
+            for chain in (B.BMGD_CHAIN_GRAPH, B.BMGD_CHAIN_LAUNCH)]
+    try:
+        assert [c.stats().chain for c in ctxs] == [B.BMGD_CHAIN_GRAPH, B.BMGD_CHAIN_LAUNCH]
+        for r in range(4):                                           # every graph is replayed on iterations 1..3
+            if r == 2:
+                for c in ctxs:
+                    c.set_lr(0.02)
+            if r == 3:
+                for c in ctxs:
+                    c.set_lr_schedule(np.linspace(0.03, 0.001, 37).astype(np.float32))
+            for k in range(w.K):
+                lo, hi = wl.buffer_rows(w, k)
+                for c in ctxs:
+                    c.run_device_buffer(xd[lo:hi], yd[lo:hi], hi - lo, s)
+                with torch.cuda.stream(s):
+                    scratch.add_(1.0)                                # the program's own work between replays
+                a, b = ctxs[0].get_theta(), ctxs[1].get_theta()      # (blocks)
+                assert np.isfinite(a).all() and np.array_equal(a, b), (r, k)
+        assert ctxs[0].stats().steps == ctxs[1].stats().steps == 4 * 2 * (8 + 8 + 3)
+    finally:
+        for c in ctxs:
+            c.close()
