@@ -185,8 +185,10 @@ def _roofline(w, delta, traffic=None):
     achieved = bytes_per_launch / per_launch_s / 1e9
     return {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
-            # rows wider than 1024 floats on eight or more workgroups run the kernel with an exchange wavefront
-            "kernel": "glm_split_kernel" if w.p > 1024 and w.p % 4 == 0 and delta["n_workgroups"] >= 8 else "glm_chain_kernel",
+            # the three persistent kernels differ in their workgroup size: 11 wavefronts (rows wider than 1024 floats:
+            # eight row wavefronts and an exchange wavefront alone on its SIMD), 12 (narrower rows whose share of a step fits
+            # the registers: eight row wavefronts and four exchange wavefronts), else the general kernel
+            "kernel": {704: "glm_split_kernel", 768: "glm_narrow_kernel"}.get(delta["threads_per_group"], "glm_chain_kernel"),
             "avg_launch_ms": round(per_launch_s * 1e3, 4),
             "algorithmic_bytes_per_launch": int(bytes_per_launch)}
 

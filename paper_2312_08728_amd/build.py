@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbmgd.so")
-SOURCES = ["bmgd_api.hip", "perm_kernel.hip", "glm_kernels.hip", "glm_split_kernel.hip", "softmax_kernels.hip", "gram_kernels.hip", "reader.hip", "noalloc.hip"]
+SOURCES = ["bmgd_api.hip", "perm_kernel.hip", "glm_kernels.hip", "glm_split_kernel.hip", "glm_narrow_kernel.hip", "softmax_kernels.hip", "gram_kernels.hip", "reader.hip", "noalloc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

@@ -97,6 +97,11 @@ struct GlmLaunchShape {
     int split;          // 1: the persistent chain runs the kernel for rows of more than 1024 floats (glm_split_kernel.hip):
                         // G is a multiple of 8, split_ch = float4 chunks of a row per lane (1: p <= 2048, 2: p <= 4096)
     int split_ch;
+    int narrow;         // 1: the persistent chain runs the kernel for rows of up to 1024 floats whose share of a step fits a
+                        // workgroup's registers (glm_narrow_kernel.hip): G is a multiple of 8, narrow_pf rows per row slot
+    int narrow_pf;
+    int64_t n;          // mini-batch size and row length the shape was planned for
+    int p;
     int chain_block;    // threads per workgroup of the persistent chain's kernel
 };
 
@@ -140,6 +145,14 @@ size_t glm_split_lds_bytes(int ch);
 int glm_split_block();
 hipError_t glm_split_prepare(int ch, bool opt, int* max_groups);
 hipError_t glm_split_launch(int ch, bool opt, int G, const GlmArgs& args, hipStream_t stream);
+
+// Persistent chain for rows of up to 1024 floats (p even) on G = 8, 16, ... workgroups when a step's rows fit the
+// registers of the grid (glm_narrow_kernel.hip).  glm_narrow_rows_in_flight: rows per row slot that a step of n rows
+// needs on G workgroups, 0 if that is more than the kernel holds.
+int glm_narrow_block();
+int glm_narrow_rows_in_flight(int v, int cpl, int L, int G, int64_t n);
+hipError_t glm_narrow_prepare(const GlmLaunchShape& shape, int p, int* max_groups);
+hipError_t glm_narrow_launch(const GlmLaunchShape& shape, const GlmArgs& args, hipStream_t stream);
 
 // Evaluation: partial[b] = sum of the per-sample losses of the rows workgroup b takes (b < nblocks <= kEvalBlocks).
 constexpr int kEvalBlocks = 1024;

@@ -62,6 +62,32 @@ __device__ __forceinline__ float slot_sum(float v, int L)
     return v;
 }
 
+// The same two sums without branches on L (every stage is executed and its result kept or dropped): for code whose
+// control flow must stay a straight line.
+__device__ __forceinline__ float group_sum_flat(float v, int L)
+{
+    float t;
+    t = dpp_mov<0xB1>(v); v += L >= 2 ? t : 0.f;
+    t = dpp_mov<0x4E>(v); v += L >= 4 ? t : 0.f;
+    t = dpp_mov<0x141>(v); v += L >= 8 ? t : 0.f;
+    t = dpp_mov<0x140>(v); v += L >= 16 ? t : 0.f;
+    t = swap16_sum(v); v = L >= 32 ? t : v;
+    t = swap32_sum(v); v = L >= 64 ? t : v;
+    return v;
+}
+
+__device__ __forceinline__ float slot_sum_flat(float v, int L)
+{
+    float t;
+    t = dpp_mov<0x121>(v); v += L <= 1 ? t : 0.f;
+    t = dpp_mov<0x122>(v); v += L <= 2 ? t : 0.f;
+    t = dpp_mov<0x124>(v); v += L <= 4 ? t : 0.f;
+    t = dpp_mov<0x128>(v); v += L <= 8 ? t : 0.f;
+    t = swap16_sum(v); v = L <= 16 ? t : v;
+    t = swap32_sum(v); v = L <= 32 ? t : v;
+    return v;
+}
+
 template <int V>
 __device__ __forceinline__ void load_vec(const float* __restrict__ src, float* dst)
 {
@@ -149,21 +175,21 @@ struct PollGuard {
     long long timeout;
     long long t0;
     unsigned misses;
-    // Called after a failed poll: backs off briefly (polls travel over the fabric; a storm of them slows
-    // the very stores they wait for), and reports true when the wait must be given up.
+    // Called after a failed poll; reports true when the wait must be given up.  Reading the clock is also the
+    // back-off (polls travel over the fabric; a storm of them slows the very stores they wait for).  The abort flag
+    // is looked at on every 32nd miss only: it lives in global memory, and a load from it costs a whole trip over
+    // the fabric, as much as the poll that just failed.
     __device__ __forceinline__ bool expired()
     {
-        __builtin_amdgcn_s_sleep(2);
-        ++misses;
-        if (misses > 2u && (misses & 31u) != 0u) return false;   // clock and flag: first misses, then every 32nd
-        if (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) return true;
         const long long now = wall_clock64();
         if (t0 == 0) t0 = now;
+        ++misses;
         if (now - t0 > timeout) {
             __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return true;
         }
-        return false;
+        if ((misses & 31u) != 0u) return false;
+        return __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
     }
     __device__ __forceinline__ void arm() { t0 = 0; misses = 0; }
 };

@@ -264,18 +264,13 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
 
     constexpr bool DB = PIPE == kPipeGroups;
     constexpr bool AHEAD = PIPE == kPipeAhead;
-    RowGroup<V, CPL, PF> cur, nxt;                   // nxt is not live with kPipeWide
+    // kPipeAhead: ga holds the rows of even steps (counted from `first`), gb those of odd steps.  Otherwise ga is
+    // the group in use and gb the look-ahead of kPipeGroups (not live with kPipeWide).
+    RowGroup<V, CPL, PF> ga, gb;
     int idxn[PF];
     load_idx(first, 0, idxn);
-    prefetch_step(first, cur, idxn);
-    if constexpr (AHEAD) prefetch_step(first + 1, nxt, idxn);
-    // after the exchange of step s: bring the rows a later step needs
-    auto advance_rows = [&](int s) {
-        if constexpr (AHEAD) {
-            cur = nxt;                               // rows of step s + 1, requested a whole step ago
-            prefetch_step(s + 2, nxt, idxn);
-        }
-    };
+    prefetch_step(first, ga, idxn);
+    if constexpr (AHEAD) prefetch_step(first + 1, gb, idxn);
 
     PollGuard guard{a.sync + 1, a.timeout_ticks, 0, 0};
 
@@ -284,7 +279,12 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
         gather_columns_impl(xc, words, c_lo, c_hi, tag, apply);
     };
 
-    for (int s = first; s < last; ++s) {
+    // Step s of the launch on the rows held in `cur`; false when the launch ends with it (a wait ran out, or the
+    // step-per-launch form has written its sums).  With kPipeAhead `cur` is refilled, once theta is known, with the
+    // rows of step s + 2: the caller alternates two groups, so that rows in flight are never copied from one set
+    // of registers to another (a copy would have to wait for them).
+    auto run_step = [&](int s, RowGroup<V, CPL, PF>& cur, RowGroup<V, CPL, PF>& nxt) __attribute__((always_inline)) -> bool {
+        (void)nxt;
         const int nb = batch_rows(s);
         const int iters = batch_iters(s);
         const unsigned tag = a.tag_base + (unsigned)(s - first) + 1u;
@@ -368,7 +368,7 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
                 for (int w = 0; w < NW; ++w) t += wpart[w * p + c];
                 part[(size_t)blockIdx.x * p + c] = t;
             }
-            return;
+            return false;
         }
         if (G == 1) {
             // single workgroup: the workgroup sum is the batch sum
@@ -378,10 +378,10 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
                 th_lds[c] = apply_update(c, c, t);
             }
             __syncthreads();
-            if constexpr (AHEAD) advance_rows(s);
+            if constexpr (AHEAD) prefetch_step(s + 2, cur, idxn);
             else if (s + 1 < last) prefetch_step(s + 1, cur, idxn);
             load_theta_regs();
-            continue;
+            return true;
         }
 
         // next step's rows do not depend on theta: in flight while the exchange resolves
@@ -401,14 +401,27 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
         if (a.reduce_mode == kReduceRedundant) {
             // every workgroup applies the same update to its own copy of theta and of the optimizer's state
             gather_columns(words, 0, p, tag, [&](int c, float t) { th_lds[c] = apply_update(c, (int)blockIdx.x * pp + c, t); });
-            if (s_abort) return;
+            if (s_abort) return false;
         } else {
             if (sliced_update(xc, words, a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp, th_lds, tag,
                               [&](int c, float t) { return apply_update(c, c, t); }))
-                return;
+                return false;
         }
-        if constexpr (AHEAD) advance_rows(s);
+        if constexpr (AHEAD) prefetch_step(s + 2, cur, idxn);
         load_theta_regs();
+        return true;
+    };
+
+    if constexpr (AHEAD) {
+        int s = first;
+        for (; s + 1 < last; s += 2) {
+            if (!run_step(s, ga, gb)) return;
+            if (!run_step(s + 1, gb, ga)) return;
+        }
+        if (s < last && !run_step(s, ga, gb)) return;
+    } else {
+        for (int s = first; s < last; ++s)
+            if (!run_step(s, ga, gb)) return;
     }
 
     if (blockIdx.x == 0 && a.single_step < 0) {
@@ -587,7 +600,20 @@ bool glm_plan(int64_t p, int64_t n, int requested_G, int num_cus, GlmLaunchShape
     }
     if (G < 1) G = 1;
     if (G > num_cus) G = num_cus;
+    // narrow rows on eight or more workgroups, a step's rows fitting the registers: the kernel with an exchange wavefront
+    // (not where the sums of all workgroups are few enough for every workgroup to add them up itself: one trip
+    // over the fabric per step instead of two)
+    if (s.CPL < 8 && s.V >= 2 && G >= 8 && (int64_t)G * p > 4096) {
+        const int pf = glm_narrow_rows_in_flight(s.V, s.CPL, s.L, G & ~7, n);
+        if (pf > 0) {
+            s.narrow = 1;
+            s.narrow_pf = pf;
+            G &= ~7;
+        }
+    }
     s.G = G;
+    s.n = n;
+    s.p = (int)p;
     // Rows each row slot must take per step.  If one register-resident group covers it, the whole next
     // batch is prefetched across the exchange (no look-ahead needed); otherwise iterate with look-ahead.
     const int64_t need = (n + (int64_t)G * slots_per_group - 1) / ((int64_t)G * slots_per_group);
@@ -599,7 +625,7 @@ bool glm_plan(int64_t p, int64_t n, int requested_G, int num_cus, GlmLaunchShape
     } else {
         s.PF = max_pf(s.V, s.CPL); s.pipe = kPipeGroups;
     }
-    s.chain_block = s.block;
+    s.chain_block = s.narrow ? glm_narrow_block() : s.block;
     if (s.CPL >= 8 && s.V == 4 && G >= 8) {
         // wide rows on eight or more workgroups: the kernel with an exchange wavefront and a two-level exchange
         s.split = 1;
@@ -647,6 +673,21 @@ hipError_t glm_prepare(GlmLaunchShape* s)
         s->split = 0;                                // not even eight fit: the kernel below takes over
         s->chain_block = s->block;
     }
+    if (s->narrow) {
+        int cap = 0;
+        e = glm_narrow_prepare(*s, s->p, &cap);
+        if (e != hipSuccess) return e;
+        cap = std::min(cap, prop.multiProcessorCount) & ~7;
+        const int G = std::min(s->G, cap) & ~7;
+        // fewer workgroups than planned hold fewer rows: only if the step still fits
+        if (G >= 8 && glm_narrow_rows_in_flight(s->V, s->CPL, s->L, G, s->n) == s->narrow_pf) {
+            s->max_G = std::min(s->max_G, cap);
+            s->G = G;
+        } else {
+            s->narrow = 0;
+            s->chain_block = s->block;
+        }
+    }
     return hipSuccess;
 }
 
@@ -657,6 +698,12 @@ hipError_t glm_launch_chain(const GlmLaunchShape& s, const GlmArgs& args, hipStr
         GlmArgs a = args;
         a.single_step = -1;
         return glm_split_launch(s.split_ch, s.with_optimizer != 0, s.G, a, stream);
+    }
+    if (s.narrow) {
+        if (s.G > s.max_G) return hipErrorInvalidValue;
+        GlmArgs a = args;
+        a.single_step = -1;
+        return glm_narrow_launch(s, a, stream);
     }
     KernelFn fn = pick_kernel(s);
     if (!fn || s.G < 1 || s.G > s.max_G) return hipErrorInvalidValue;

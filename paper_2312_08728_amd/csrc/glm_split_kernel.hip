@@ -16,24 +16,15 @@
 //     rows of the next step keep arriving.  Loads return to a wavefront in the order it issued them, so a wavefront
 //     that has rows in flight must not poll for the exchange (its poll would come back behind its newest rows):
 //     row wavefronts issue no load but their rows (and, right behind them, the responses and the next row indices), and
-//   * a ninth wavefront does the exchange.  It has no rows in flight, so its polls return at the latency of the
-//     fabric, and it asks for everything a phase needs in one trip (32 loads of 16 bytes per lane in flight):
-//       1. every row wavefront stores its slice of the workgroup's gradient sums as flagged words {value : tag};
-//       2. the exchange wavefront of workgroup g adds up, for the g-th slice of the columns (whole 128-byte lines of
-//          words), the words of all G workgroups in a fixed order, applies the update to its slice of theta and
-//          publishes the new values in eight copies of theta (a workgroup later reads the copy b mod 8, so no set
-//          of words is polled by the whole grid);
-//       3. every exchange wavefront collects the whole new theta from its copy into shared memory and raises the
-//          version flag the row wavefronts wait on.
-//     Two trips over the fabric per step.  (Measured: under the row traffic a trip costs about 2 us whether the words
-//     come from the same die or another, and a wavefront that asks for a phase's words in two batches pays twice, so
-//     a die-local first stage - one more trip - loses; loads that would be served from a die's L2 without leaving
-//     it, other than atomics, do not exist in this mode of the hardware.)
+//   * a ninth wavefront does the exchange (glm_exchange.h).  It has no rows in flight, so its polls return at the latency
+//     of the fabric.  Two trips over the fabric per step.  (Measured: under the row traffic a trip costs about 2 us
+//     whether the words come from the same die or another, and a wavefront that asks for a phase's words in two
+//     batches pays twice, so a die-local first stage - one more trip - loses; loads that would be served from a
+//     die's L2 without leaving it, other than atomics, do not exist in this mode of the hardware.)
 //
 // Waits: row wavefronts only ever wait on shared-memory flags (which the exchange wavefront always releases, also
 // when it gives up); the exchange wavefront's polls are bounded by the wall clock (PollGuard).
-#include "bmgd_internal.h"
-#include "glm_device.h"
+#include "glm_exchange.h"
 
 #include <algorithm>
 
@@ -41,62 +32,9 @@ namespace bmgd {
 
 namespace {
 
-constexpr int kRowWaves = 8;
-// Eleven wavefronts are launched and three roles handed out by wavefront index.  The hardware deals the wavefronts of a
-// workgroup out to the four SIMDs of a compute unit in turn (0, 4, 8 share the first one), and every SIMD feeds its memory
-// instructions into a queue of its own, in order.  The exchange wavefront must not stand in such a queue behind row
-// loads, so it is wavefront 0 and its two SIMD mates (4 and 8) leave right after the start-up barrier; the other
-// eight are the row wavefronts.  (Only speed depends on the dealing order; the roles are correct for any.)
-constexpr int kSplitWaves = 11;
-constexpr int kSplitBlock = 64 * kSplitWaves;
+constexpr int kSplitBlock = kRoleBlock;
 constexpr int kGroupRows = 4;                        // rows whose partial dot products are exchanged together
 constexpr int kGroups = 3;                           // groups of rows a row wavefront holds (used, or in flight)
-
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) float lds_f32;
-typedef __attribute__((address_space(3))) unsigned lds_u32;
-
-constexpr int kAgentScope = 0x10;                    // cache policy of a buffer instruction: sc1
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t words_rsrc(const void* base, size_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
-}
-
-// (A function, so that its argument is a scalar copy: bit-casting an element of a vector in place reads element 0.)
-__device__ __forceinline__ float as_float(unsigned v) { return __builtin_bit_cast(float, v); }
-
-// two flagged words next to each other: {value, tag, value, tag}
-__device__ __forceinline__ u32x4 word_pair(float v0, float v1, unsigned tag)
-{
-    u32x4 w;
-    w.x = __builtin_bit_cast(unsigned, v0); w.y = tag;
-    w.z = __builtin_bit_cast(unsigned, v1); w.w = tag;
-    return w;
-}
-
-// The two waits of a row wavefront, each written as one block of assembly.  The compiler must see no loop and no
-// branch out of the row loop at these places: it keeps count of the row loads in flight per path through the
-// control-flow graph, and every extra path (a poll loop, an early exit, which the structuriser routes through the
-// loop's latch) makes it wait for rows that the path actually taken does not need.
-// Wait until the word at shared-memory address `addr` is >= want, or the word at `abort_addr` is non-zero.
-__device__ __forceinline__ void lds_wait_ge(unsigned addr, unsigned want, unsigned abort_addr)
-{
-    unsigned t;
-    asm volatile("1:\n\t"
-                 "ds_read_b32 %0, %1\n\t"
-                 "s_waitcnt lgkmcnt(0)\n\t"
-                 "v_cmp_ge_u32_e32 vcc, %0, %2\n\t"
-                 "s_cbranch_vccnz 2f\n\t"
-                 "ds_read_b32 %0, %3\n\t"
-                 "s_waitcnt lgkmcnt(0)\n\t"
-                 "v_cmp_ne_u32_e32 vcc, 0, %0\n\t"
-                 "s_cbranch_vccnz 2f\n\t"
-                 "s_sleep 1\n\t"
-                 "s_branch 1b\n"
-                 "2:"
-                 : "=&v"(t) : "v"(addr), "v"(want), "v"(abort_addr) : "vcc", "memory");
-}
 
 // Wait until every lane's word (one address per lane) equals want, or the word at `abort_addr` is non-zero.
 __device__ __forceinline__ void lds_wait_all_eq(unsigned addr, unsigned want, unsigned abort_addr)
@@ -141,7 +79,6 @@ __global__ void __launch_bounds__(kSplitBlock) glm_split_kernel(GlmArgs a)
     volatile lds_u32* pd_seq = (volatile lds_u32*)(smem + 2 * P_PAD + 2 * kRowWaves * GR);   // [2][kRowWaves]: their sequence numbers
     lds_f32* red = (lds_f32*)(smem + 2 * P_PAD + 2 * kRowWaves * GR + 2 * kRowWaves);   // [64][2] scratch of the exchange wavefront
     lds_f32* sums = red + 2 * 64;                    // [P_PAD]: the workgroup's gradient sums of a step, on their way out
-    const int M = (a.rows + a.n - 1) / a.n;
     const int first = a.s_begin, last = a.s_end;
 
     // both copies of theta: columns beyond p stay zero for good (rows are read at column 0 there)
@@ -150,23 +87,14 @@ __global__ void __launch_bounds__(kSplitBlock) glm_split_kernel(GlmArgs a)
     if (tid == 0) { s_abort = 0; s_theta_version = 0u; s_published = 0u; }
     __syncthreads();                                 // the only barrier: from here on the wavefronts meet through flags
 
-    const float rcpM = 1.0f / (float)M;
-    auto split = [&](int s, int& t, int& m) {        // s = t M + m, exact for s < 2^23
-        t = (int)((float)s * rcpM);
-        m = s - t * M;
-        if (m >= M) { m -= M; ++t; }
-        if (m < 0) { m += M; --t; }
-    };
-    const int n_tail = a.rows - (M - 1) * a.n;
-    auto batch_rows = [&](int s) { int t, m; split(s, t, m); return m == M - 1 ? n_tail : a.n; };
-    auto batch_base = [&](int s) { int t, m; split(s, t, m); return (size_t)t * (size_t)a.perm_stride + (size_t)m * (size_t)a.n; };
-    const unsigned words_bytes = (unsigned)((size_t)G * pp * 8);
-    const unsigned copies_bytes = (unsigned)((size_t)kThetaCopies * pp * 8);
+    const StepGeometry geo(a);
+    auto batch_rows = [&](int s) { return geo.batch_rows(s); };
+    auto batch_base = [&](int s) { return geo.batch_base(s); };
 
-    if (wave == 4 || wave == 8) return;              // they only keep the exchange wavefront's SIMD free of row loads
-    if (wave != 0) {
+    const int rw = role_of(wave);
+    if (rw == -2) return;                            // they only keep the exchange wavefront's SIMD free of row loads
+    if (rw >= 0) {
         // ------------------------------------------------------------------------------------ row wavefronts
-        const int rw = wave - 1 - (wave >> 2);       // 1, 2, 3, 5, 6, 7, 9, 10 -> 0 .. 7
         // Workgroup g takes rows g, g + G, g + 2 G, ... of a mini-batch, in groups of GR; a step has at least one
         // group (a group without rows contributes nothing), so every step ends with a publication.
         auto groups_of = [&](int s) {
@@ -316,166 +244,9 @@ __global__ void __launch_bounds__(kSplitBlock) glm_split_kernel(GlmArgs a)
     }
 
     // ------------------------------------------------------------------------------------ exchange wavefront
-    // Workgroup g owns the columns [c_lo, c_hi) of theta (whole 128-byte lines of words, so no line has two writers).
-    const int cw = (((p + G - 1) / G) + 15) & ~15;
-    const int c_lo = min(p, g * cw), c_hi = min(p, c_lo + cw);
-    const int npair = cw / 2;                        // column pairs of a slice (a multiple of 8)
-    const int PPc = min(npair, 64);                  // pairs taken side by side by the lanes ...
-    const int SG = 64 / PPc;                         // ... by SG groups of lanes, each group taking every SG-th workgroup
-    const int my_pair = lane % PPc, my_sg = lane / PPc;
-    const bool lane_used = my_sg < SG;
-    PollGuard guard{a.sync + 1, a.timeout_ticks, 0, 0};
-    bool dead = false;
-    constexpr int U = 32;                            // pairs of words requested per trip over the fabric
-    for (int s = first; s < last && !dead; ++s) {
-        const unsigned tag = a.tag_base + (unsigned)(s - first) + 1u;
-        const float alpha_s = a.lr_tab ? a.lr_tab[min(a.lr_base + s, a.lr_len - 1)] : a.alpha;
-        const int nb = batch_rows(s);
-        const float scale = alpha_s / (float)nb;
-        const unsigned ver = (unsigned)(s - first);
-        const lds_f32* th_old = th + (ver & 1u) * P_PAD;
-        lds_f32* th_new = th + ((ver + 1u) & 1u) * P_PAD;
-        float oc1 = 1.f, oc2 = 1.f;
-        if constexpr (OPT) {
-            if (a.opt.kind == kOptAdam) opt_corrections(a.opt, a.opt.k_base + (s - first) + 1, oc1, oc2);
-        }
-        // This workgroup's own rows first: until they have been summed nothing can be complete, and polling the
-        // fabric meanwhile would only take bandwidth from the rows.  A wait on shared memory alone (the wall clock is
-        // looked at now and then): a load from global memory here would return after microseconds.
-        {
-            long long t0 = 0;
-            unsigned spins = 0u;
-            while (__hip_atomic_load(&s_published, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < (ver + 1u) * kRowWaves) {
-                __builtin_amdgcn_s_sleep(1);
-                if ((++spins & 1023u) == 0u) {
-                    const long long now = wall_clock64();
-                    if (t0 == 0) t0 = now;
-                    if (now - t0 > a.timeout_ticks ||
-                        __hip_atomic_load(a.sync + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) { dead = true; break; }
-                }
-            }
-        }
-        if (dead) break;
-        guard.arm();
-        const __amdgpu_buffer_rsrc_t part = words_rsrc(a.ll_part + (size_t)(s & 1) * G * pp, words_bytes);
-        // 0. this workgroup's sums out of shared memory, as flagged words: what the others wait for
-        asm volatile("" ::: "memory");
-#pragma unroll 8
-        for (int c = 2 * lane; c < p; c += 128)
-            __builtin_amdgcn_raw_buffer_store_b128(word_pair(sums[c], sums[c + 1], tag), part, (unsigned)(((size_t)g * pp + c) * 8), 0, kAgentScope);
-        const __amdgpu_buffer_rsrc_t thw = words_rsrc(a.ll_theta + (size_t)(s & 1) * kThetaCopies * pp, copies_bytes);
-
-        // 1. this workgroup's slice: sum over all workgroups, in a fixed order; the update; the new values into every
-        //    copy of theta (a workgroup reads the copy of its die, so no set of words is polled by the whole grid)
-        for (int pb = 0; pb < npair && !dead; pb += PPc) {
-            const int c = c_lo + 2 * (pb + my_pair);
-            const bool mine = lane_used && c < c_hi;             // (the slice ends on a multiple of 16 or at p, and p is even)
-            // One address register per lane (its pair of columns in the row of words of workgroup my_sg); what differs
-            // between a lane's loads is uniform and goes into the scalar offset.  G is a multiple of SG, so whether a
-            // load is beyond the last workgroup is uniform too (such loads repeat the last group and are not added).
-            const unsigned voff = (unsigned)min(c, p - 2) * 8u + (unsigned)my_sg * (unsigned)(pp * 8);
-            float t0 = 0.f, t1 = 0.f;
-            for (int i0 = 0; i0 < G && !dead; i0 += SG * U) {
-                u32x4 w[U];
-                for (;;) {
-                    asm volatile("" ::: "memory");
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        w[u] = __builtin_amdgcn_raw_buffer_load_b128(part, voff, (unsigned)min(i0 + SG * u, G - SG) * (unsigned)(pp * 8), kAgentScope);
-                    asm volatile("" ::: "memory");
-                    unsigned miss = 0u;
-#pragma unroll
-                    for (int u = 0; u < U; ++u) miss |= (w[u].y ^ tag) | (w[u].w ^ tag);
-                    if (!mine) miss = 0u;
-                    if (__builtin_amdgcn_ballot_w64(miss != 0u) == 0ull) break;
-                    if (guard.expired()) { dead = true; break; }
-                }
-                if (dead) break;
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (i0 + SG * u < G) {
-                        t0 += as_float(w[u].x);
-                        t1 += as_float(w[u].z);
-                    }
-            }
-            if (dead) break;
-            // the SG groups' sums meet in shared memory (this wavefront alone uses `red`; its requests are served in order)
-            if (lane_used) {
-                red[(my_sg * PPc + my_pair) * 2] = t0;
-                red[(my_sg * PPc + my_pair) * 2 + 1] = t1;
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            if (lane < PPc && c < c_hi) {
-                float b0 = 0.f, b1 = 0.f;
-                for (int q = 0; q < SG; ++q) {
-                    b0 += red[(q * PPc + lane) * 2];
-                    b1 += red[(q * PPc + lane) * 2 + 1];
-                }
-                float n0, n1;
-                if constexpr (!OPT) {
-                    n0 = th_old[c] - scale * b0;
-                    n1 = th_old[c + 1] - scale * b1;
-                } else {
-                    float m0 = a.opt.m[c], m1 = a.opt.m[c + 1];
-                    float s0 = a.opt.kind == kOptAdam ? a.opt.s[c] : 0.f, s1 = a.opt.kind == kOptAdam ? a.opt.s[c + 1] : 0.f;
-                    n0 = opt_update(a.opt, th_old[c], b0 / (float)nb, alpha_s, m0, s0, oc1, oc2);
-                    n1 = opt_update(a.opt, th_old[c + 1], b1 / (float)nb, alpha_s, m1, s1, oc1, oc2);
-                    a.opt.m[c] = m0; a.opt.m[c + 1] = m1;
-                    if (a.opt.kind == kOptAdam) { a.opt.s[c] = s0; a.opt.s[c + 1] = s1; }
-                }
-                const u32x4 nw = word_pair(n0, n1, tag);
-#pragma unroll
-                for (int r = 0; r < kThetaCopies; ++r)
-                    __builtin_amdgcn_raw_buffer_store_b128(nw, thw, (unsigned)c * 8u, (unsigned)(r * pp * 8), kAgentScope);
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // `red` is reused by the next chunk of pairs
-        }
-        if (dead) break;
-        // 2. the whole new theta, from the copy of this workgroup's die
-        // (one address register per lane again; loads beyond the row of words are answered with zeros by the buffer's
-        // range check and are not looked at)
-        const unsigned copy_off = (unsigned)((g % kThetaCopies) * pp * 8) + (unsigned)lane * 16u;
-        for (int c0 = 0; c0 < p && !dead; c0 += 2 * 64 * U) {
-            u32x4 w[U];
-            for (;;) {
-                asm volatile("" ::: "memory");
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    w[u] = __builtin_amdgcn_raw_buffer_load_b128(thw, copy_off, (unsigned)(c0 + 128 * u) * 8u, kAgentScope);
-                asm volatile("" ::: "memory");
-                unsigned miss = 0u;
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (c0 + 2 * (lane + 64 * u) < p) miss |= (w[u].y ^ tag) | (w[u].w ^ tag);
-                if (__builtin_amdgcn_ballot_w64(miss != 0u) == 0ull) break;
-                if (guard.expired()) { dead = true; break; }
-            }
-            if (dead) break;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int c = c0 + 2 * (lane + 64 * u);
-                if (c < p) {
-                    th_new[c] = as_float(w[u].x);
-                    th_new[c + 1] = as_float(w[u].z);
-                }
-            }
-        }
-        if (dead) break;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        if (lane == 0) __hip_atomic_store(&s_theta_version, ver + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    }
-    if (dead) {
-        if (lane == 0) {
-            __hip_atomic_store(a.sync + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&s_abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
-        return;
-    }
-    if (g == 0) {
-        const lds_f32* fin = th + ((unsigned)(last - first) & 1u) * P_PAD;
-        for (int c = lane; c < p; c += 64) a.theta[c] = fin[c];
-    }
+    const ExchangeLds x{th, P_PAD, red, sums, 1, P_PAD, (unsigned)kRowWaves,
+                        (lds_u32*)&s_published, (lds_u32*)&s_theta_version, (lds_i32*)&s_abort, nullptr, nullptr};
+    exchange_wavefront<OPT, 1, 32, 32>(a, x, lane, 0);
 }
 
 using KernelFn = void (*)(GlmArgs);

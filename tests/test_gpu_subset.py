@@ -88,7 +88,12 @@ def test_subset_in_the_moment_form_with_repeats_and_one_shot():
     with pytest.raises(B.BmgdError) as e:
         ctx.get_theta()
     assert e.value.code == B.BMGD_EINVAL
-    ctx.run_device_buffer(xd[:3000], yd[:3000], 3000, s)             # the context is usable again
+    # theta is not valid after that run: further runs are refused until it has been set again, then all is as before
+    with pytest.raises(B.BmgdError) as e:
+        ctx.run_device_buffer(xd[:3000], yd[:3000], 3000, s)
+    assert e.value.code == B.BMGD_ESTATE
+    ctx.set_theta(np.zeros(w.p, dtype=np.float32))
+    ctx.run_device_buffer(xd[:3000], yd[:3000], 3000, s)
     ctx.sync()
     assert B.bmgd_set_row_subset(ctx.h, None, 5) == B.BMGD_EINVAL
     assert B.bmgd_set_row_subset(ctx.h, sd, 3001) == B.BMGD_EINVAL
