@@ -159,7 +159,7 @@ def _roofline(w, delta, traffic=None):
                 "frac": round(achieved / 2500.0, 5), "traffic": None,
                 "kernel": "gemm_nt_kernel (logits, gradient+update) + softmax_residual_kernel"}
     bytes_per_launch = _algorithmic_bytes_per_sample_gradient(w) * delta["sample_gradients"] / max(delta["chain_launches"], 1)
-    if delta.get("chain") == 3:
+    if delta.get("chain") in (3, 5):
         # Least squares in the form of eq. (3.1): the rows are read by the kernel that forms the moment matrices
         # of the mini-batches, the updates are applied by the one-workgroup chain kernel.  One launch of each per
         # buffer, and the two kernels of consecutive buffers overlap: the rate is the buffer's algorithmic bytes over
@@ -171,7 +171,8 @@ def _roofline(w, delta, traffic=None):
         q = w.p + 1
         return {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
-                "kernel": "gram_chain_kernel" if per_launch_s >= prep_s else "gram_mfma_kernel",
+                "kernel": ("affine_pair_kernel (rounds of products)" if delta.get("chain") == 5 else "gram_chain_kernel")
+                          if per_launch_s >= prep_s else "gram_mfma_kernel",
                 "avg_launch_ms": round(dominant_s * 1e3, 4),
                 "algorithmic_bytes_per_launch": int(bytes_per_launch),
                 "moments_kernel": {"avg_launch_ms": round(prep_s * 1e3, 4),
@@ -181,7 +182,8 @@ def _roofline(w, delta, traffic=None):
                 "chain_kernel": {"avg_launch_ms": round(per_launch_s * 1e3, 4),
                                  "us_per_minibatch_update": round(per_launch_s * 1e6 / steps_per_launch, 4),
                                  "moment_bytes_GBs": round(steps_per_launch * (w.p + 1) * w.p * 4 / per_launch_s / 1e9, 1),
-                                 "note": "one workgroup; bound by a single compute unit's load path"}}
+                                 "note": "the steps of a launch multiplied together in log2 rounds, then applied once"
+                                         if delta.get("chain") == 5 else "one workgroup; bound by a single compute unit's load path"}}
     achieved = bytes_per_launch / per_launch_s / 1e9
     return {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic,
@@ -520,7 +522,7 @@ def main() -> int:
 
     if not args.no_others:
         others = {}
-        side = [("cfg1", 5, 0, 5), ("cfg2", 10, 0, 20), ("cfg2", 10, 1, 10), ("cfg3", 2, 0, 4), ("cfg4", 2, 0, 4),
+        side = [("cfg1", 5, 0, 5), ("cfg2", 10, 0, 20), ("cfg2", 10, 1, 10), ("cfg2", 10, 5, 20), ("cfg3", 2, 0, 4), ("cfg4", 2, 0, 4),
                 ("cfg4_full_batch", 1, 0, 1), ("cfg5", 1, 0, 1)]
         for name, nbuf, chain, nsteps in side:
             if name == w.name and chain == args.chain:
@@ -538,6 +540,8 @@ def main() -> int:
                 odt, od, _ = _time_resident(wo, ob, nsteps, 1, chain)
                 if chain == 1:
                     name += "_row_form"          # the same workload with the updates taken row by row (eq. (2.1))
+                if chain == 5:
+                    name += "_step_products"     # the moment form with the steps of a launch multiplied together (eq. (3.2))
                 rf = _roofline(wo, od)
                 others[name] = {"value": round(od["sample_gradients"] / odt, 1), "ms_per_step": round(odt * 1e3 / nsteps, 4),
                                 "us_per_minibatch_update": round(odt * 1e6 / od["minibatch_steps"], 3),
@@ -575,33 +579,38 @@ def main() -> int:
                 del Xo, yo
             except Exception as e:
                 others["cfg2_reader_and_adaptive_passes"] = {"error": str(e)[:200]}
-        try:
-            # cfg2 under fixed partitions (Section 3.1.1) with the moment matrices of every buffer cached: after the first
-            # iteration a buffer costs its chain of updates only, and no row is read or copied
-            wo = wl.CONFIGS["cfg2"]
-            ob = _device_buffers(wo, wo.K)
-            ctx = B.Context(wo.p, wo.N0, wo.n, wo.alpha, wo.T, seed=wo.seed, reshuffle=B.BMGD_RESHUFFLE_FIXED, n_buffers=wo.K,
-                            cache_moments=True)
-            _, s = _streams()
-            for Xb, yb, rows in ob:
-                ctx.run_device_buffer(Xb, yb, rows, s)
-            ctx.sync()
-            st0 = ctx.stats()
-            t0 = time.perf_counter()
-            for _ in range(4 * wo.K):
-                ctx.run_cached_buffer(s)
-            ctx.sync()
-            odt = time.perf_counter() - t0
-            st1 = ctx.stats()
-            ctx.close()
-            others["cfg2_fixed_partitions_cached_moments"] = {
-                "value": round((st1.sample_gradients - st0.sample_gradients) / odt, 1), "ms_per_step": round(odt * 1e3 / (4 * wo.K), 4),
-                "us_per_minibatch_update": round(odt * 1e6 / (st1.steps - st0.steps), 3),
-                "note": "iterations after the first: chain of eq. (3.1) only", "data": "synthetic, drawn on the device"}
-            del ob
-            torch.cuda.empty_cache()
-        except Exception as e:
-            others["cfg2_fixed_partitions_cached_moments"] = {"error": str(e)[:200]}
+        # cfg2 under fixed partitions (Section 3.1.1) with the moment matrices of every buffer cached: after the first
+        # iteration a buffer costs its chain of updates only, and no row is read or copied.  With BMGD_CHAIN_PRODUCT the
+        # product of a buffer's steps is kept as well (same rate, same passes): a buffer then costs one small matrix-vector
+        # product.
+        for key, chain_mode, note in (("cfg2_fixed_partitions_cached_moments", 0, "iterations after the first: chain of eq. (3.1) only"),
+                                      ("cfg2_fixed_partitions_cached_products", 5,
+                                       "iterations after the first: the kept product of a buffer's steps (eq. (3.2)) applied once")):
+            try:
+                wo = wl.CONFIGS["cfg2"]
+                ob = _device_buffers(wo, wo.K)
+                ctx = B.Context(wo.p, wo.N0, wo.n, wo.alpha, wo.T, seed=wo.seed, reshuffle=B.BMGD_RESHUFFLE_FIXED, n_buffers=wo.K,
+                                cache_moments=True, chain=chain_mode)
+                _, s = _streams()
+                for Xb, yb, rows in ob:
+                    ctx.run_device_buffer(Xb, yb, rows, s)
+                ctx.sync()
+                st0 = ctx.stats()
+                t0 = time.perf_counter()
+                for _ in range(4 * wo.K):
+                    ctx.run_cached_buffer(s)
+                ctx.sync()
+                odt = time.perf_counter() - t0
+                st1 = ctx.stats()
+                ctx.close()
+                others[key] = {
+                    "value": round((st1.sample_gradients - st0.sample_gradients) / odt, 1), "ms_per_step": round(odt * 1e3 / (4 * wo.K), 4),
+                    "us_per_minibatch_update": round(odt * 1e6 / (st1.steps - st0.steps), 3),
+                    "note": note, "data": "synthetic, drawn on the device"}
+                del ob
+                torch.cuda.empty_cache()
+            except Exception as e:
+                others[key] = {"error": str(e)[:200]}
         result["other_workloads"] = others
 
     print(json.dumps(result))

@@ -110,11 +110,20 @@ enum {
                                     read once), and the sequential chain then runs inside one workgroup at p^2
                                     multiply-adds per step.  Same result as the row form up to the order of
                                     summation.  BMGD_CHAIN_AUTO picks it when it applies and batch_n >= 2 p. */
-    BMGD_CHAIN_GRAPH = 4         /* softmax only (its BMGD_CHAIN_AUTO): the launches of one pass over one buffer - the transpose of
+    BMGD_CHAIN_GRAPH = 4,        /* softmax only (its BMGD_CHAIN_AUTO): the launches of one pass over one buffer - the transpose of
                                     its mini-batches, then logits, residual and gradient + update per mini-batch - are captured
                                     once into a HIP graph per (buffer address, rows, partition slot) and replayed; learning
                                     rate and update counts are read from device memory, so a replay needs no new capture.
                                     BMGD_CHAIN_LAUNCH issues the same launches one by one. */
+    BMGD_CHAIN_PRODUCT = 5       /* least squares with p <= 128 and plain steps (BMGD_OPT_SGD) only: the moment form of
+                                    BMGD_CHAIN_GRAM with the steps of a launch multiplied together.  A step of eq. (3.1) is the
+                                    affine map [theta; 1] <- A_m [theta; 1], A_m = [[I - alpha Sxx_m, alpha Sxy_m], [0, 1]], and
+                                    no A_m depends on theta, so the estimate after the steps of up to four passes is the
+                                    product A_N ... A_1 applied once (the products of eq. (3.2)); the product is formed pairwise
+                                    in log2 N rounds of small dense products on the matrix cores.  Same result as the chain up
+                                    to the order of the fp32 operations; intermediate estimates are never formed.  Needs scratch
+                                    for N / 2 + N / 4 matrices of (p + 1 rounded up to 16)^2 floats, twice; rejected if that
+                                    exceeds 1 GiB.  Never picked by BMGD_CHAIN_AUTO. */
 };
 
 /* update rule fed with the mini-batch gradient g of eq. (2.1) (Section 4.3 combines the buffering idea with NAG and

@@ -21,7 +21,7 @@ BMGD_OK, BMGD_EINVAL, BMGD_ESTATE, BMGD_EHIP, BMGD_ENOMEM = 0, 1, 2, 3, 4
 BMGD_LINEAR, BMGD_LOGISTIC, BMGD_SOFTMAX = 0, 1, 2
 BMGD_F32, BMGD_BF16 = 0, 1
 BMGD_RESHUFFLE_PER_PASS, BMGD_RESHUFFLE_FIXED = 0, 1
-BMGD_CHAIN_AUTO, BMGD_CHAIN_PERSISTENT, BMGD_CHAIN_LAUNCH, BMGD_CHAIN_GRAM, BMGD_CHAIN_GRAPH = 0, 1, 2, 3, 4
+BMGD_CHAIN_AUTO, BMGD_CHAIN_PERSISTENT, BMGD_CHAIN_LAUNCH, BMGD_CHAIN_GRAM, BMGD_CHAIN_GRAPH, BMGD_CHAIN_PRODUCT = 0, 1, 2, 3, 4, 5
 BMGD_OPT_SGD, BMGD_OPT_MOMENTUM, BMGD_OPT_NAG, BMGD_OPT_ADAM = 0, 1, 2, 3
 
 EXPORTS = [

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbmgd.so")
-SOURCES = ["bmgd_api.hip", "perm_kernel.hip", "glm_kernels.hip", "glm_split_kernel.hip", "glm_narrow_kernel.hip", "softmax_kernels.hip", "gram_kernels.hip", "reader.hip", "noalloc.hip"]
+SOURCES = ["bmgd_api.hip", "perm_kernel.hip", "glm_kernels.hip", "glm_split_kernel.hip", "glm_narrow_kernel.hip", "softmax_kernels.hip", "gram_kernels.hip", "gram_products.hip", "reader.hip", "noalloc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
@@ -41,7 +41,7 @@ def build(verbose: bool = True) -> str:
 
     # the sources are independent: compile them side by side (a handful of processes)
     from concurrent.futures import ThreadPoolExecutor
-    with ThreadPoolExecutor(max_workers=min(len(SOURCES), 7)) as pool:
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), 8)) as pool:
         objs = list(pool.map(compile_one, SOURCES))
     cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:

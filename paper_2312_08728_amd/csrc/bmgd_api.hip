@@ -33,7 +33,7 @@ constexpr int kMaxGroups = 256;                    // upper bound used to size t
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, sm_state, wbt, u, rt, xt, gram[2], gram_perm, gram_cache, gram_cache_set, opt_m, opt_s, opt_len, eval, swa, total;
+    size_t slot_x[2], slot_y[2], perm, theta, partial, ll_part, ll_theta, sync, sm_state, wbt, u, rt, xt, gram[2], prod[2], gram_perm, gram_cache, gram_cache_set, prod_cache, prod_cache_set, opt_m, opt_s, opt_len, eval, swa, total;
 };
 
 struct Slot {
@@ -88,14 +88,23 @@ struct bmgd_ctx {
     // stream and the one-workgroup chain on a stream of the library's own, so that the pre-pass of the next
     // buffer overlaps the chain of this one; two sets of partitions and matrices alternate.
     float* gram[2] = {nullptr, nullptr};
+    bool products = false;                         // BMGD_CHAIN_PRODUCT: the steps of a launch multiplied together (gram_products.hip)
+    float* prod[2] = {nullptr, nullptr};
+    int psel = 0;
     int32_t* gram_perm[2] = {nullptr, nullptr};
     struct CachedMoments {                         // moment matrices of buffer index k under its fixed partition
         bool valid = false;
+        // BMGD_CHAIN_PRODUCT: the product of the steps of a run over this buffer, kept as well while it stays the same
+        // (made with this rate and this number of passes, no table of rates)
+        bool prod_valid = false;
+        float prod_alpha = 0.f;
+        int prod_np = 0;
         int64_t rows = 0;
         hipEvent_t ready = nullptr;                // completes when the kernel that formed them has
     };
     std::vector<CachedMoments> mcache;             // [n_buffers] when cfg.cache_moments
     char* gram_cache = nullptr;
+    char* prod_cache = nullptr;
     hipEvent_t cache_chain_done = nullptr;         // behind the latest chain that read the cache
     hipStream_t chain_stream = nullptr;
     hipEvent_t prep_done[2] = {nullptr, nullptr};  // stop event of the moment kernel that filled set i (owned by open_prep)
@@ -160,13 +169,20 @@ bool valid_config(const bmgd_config& c, std::string* why)
     if (c.reshuffle != BMGD_RESHUFFLE_PER_PASS && c.reshuffle != BMGD_RESHUFFLE_FIXED) return bad("unknown reshuffle mode");
     if (c.n_buffers < 0) return bad("n_buffers must be non-negative");
     if (c.chain != BMGD_CHAIN_AUTO && c.chain != BMGD_CHAIN_PERSISTENT && c.chain != BMGD_CHAIN_LAUNCH &&
-        c.chain != BMGD_CHAIN_GRAM && c.chain != BMGD_CHAIN_GRAPH)
+        c.chain != BMGD_CHAIN_GRAM && c.chain != BMGD_CHAIN_GRAPH && c.chain != BMGD_CHAIN_PRODUCT)
         return bad("unknown chain mode");
     if (c.chain == BMGD_CHAIN_GRAPH && c.model != BMGD_SOFTMAX) return bad("BMGD_CHAIN_GRAPH is the softmax model's mode");
-    if (c.model == BMGD_SOFTMAX && (c.chain == BMGD_CHAIN_PERSISTENT || c.chain == BMGD_CHAIN_GRAM))
+    if (c.model == BMGD_SOFTMAX && (c.chain == BMGD_CHAIN_PERSISTENT || c.chain == BMGD_CHAIN_GRAM || c.chain == BMGD_CHAIN_PRODUCT))
         return bad("softmax runs with BMGD_CHAIN_AUTO, BMGD_CHAIN_GRAPH or BMGD_CHAIN_LAUNCH");
-    if (c.chain == BMGD_CHAIN_GRAM && (c.model != BMGD_LINEAR || c.p > kGramMaxP))
-        return bad("BMGD_CHAIN_GRAM needs the linear model and p <= 128");
+    if ((c.chain == BMGD_CHAIN_GRAM || c.chain == BMGD_CHAIN_PRODUCT) && (c.model != BMGD_LINEAR || c.p > kGramMaxP))
+        return bad("BMGD_CHAIN_GRAM and BMGD_CHAIN_PRODUCT need the linear model and p <= 128");
+    if (c.chain == BMGD_CHAIN_PRODUCT) {
+        // the steps of a launch are multiplied together: plain steps only, and the products' scratch has to stay reasonable
+        if (c.optimizer != BMGD_OPT_SGD) return bad("BMGD_CHAIN_PRODUCT applies to plain steps only (BMGD_OPT_SGD)");
+        const int64_t steps = (int64_t)kMaxPassesPerLaunch * ((c.buffer_n + c.batch_n - 1) / c.batch_n);
+        if (gram_products_scratch_floats(c.p, steps) > (size_t(1) << 28))
+            return bad("BMGD_CHAIN_PRODUCT: too many mini-batches per buffer (its scratch would exceed 1 GiB); use a larger batch_n");
+    }
     if (c.n_workgroups < 0 || c.n_workgroups > kMaxGroups) return bad("n_workgroups must be in [0, 256]");
     if (c.barrier_timeout_us < 0) return bad("barrier_timeout_us must be non-negative");
     if (c.optimizer < BMGD_OPT_SGD || c.optimizer > BMGD_OPT_ADAM) return bad("unknown optimizer");
@@ -174,8 +190,8 @@ bool valid_config(const bmgd_config& c, std::string* why)
     if (c.cache_moments) {
         if (c.reshuffle != BMGD_RESHUFFLE_FIXED || c.n_buffers < 1 || c.n_buffers > 65536)
             return bad("cache_moments needs BMGD_RESHUFFLE_FIXED and 1 <= n_buffers <= 65536");
-        if (c.model != BMGD_LINEAR || c.p > kGramMaxP || (c.chain != BMGD_CHAIN_GRAM && !(c.chain == BMGD_CHAIN_AUTO && c.batch_n >= 2 * c.p)))
-            return bad("cache_moments needs the moment form (BMGD_CHAIN_GRAM, or BMGD_CHAIN_AUTO with batch_n >= 2 p)");
+        if (c.model != BMGD_LINEAR || c.p > kGramMaxP || (c.chain != BMGD_CHAIN_GRAM && c.chain != BMGD_CHAIN_PRODUCT && !(c.chain == BMGD_CHAIN_AUTO && c.batch_n >= 2 * c.p)))
+            return bad("cache_moments needs the moment form (BMGD_CHAIN_GRAM, BMGD_CHAIN_PRODUCT, or BMGD_CHAIN_AUTO with batch_n >= 2 p)");
     }
     if (c.optimizer == BMGD_OPT_MOMENTUM || c.optimizer == BMGD_OPT_NAG) {
         if (!(c.momentum >= 0.0 && c.momentum < 1.0)) return bad("momentum must be in [0, 1)");
@@ -234,17 +250,32 @@ Layout make_layout(const bmgd_config& c)
     l.gram[0] = l.gram[1] = l.gram_perm = off;
     if (resolve_chain(c) == BMGD_CHAIN_GRAM) {
         const size_t set = align_up((size_t)kMaxPassesPerLaunch * (size_t)((c.buffer_n + c.batch_n - 1) / c.batch_n) *
-                                    gram_bytes_per_batch(c.p));
+                                    (c.chain == BMGD_CHAIN_PRODUCT ? gram_dense_bytes_per_batch(c.p) : gram_bytes_per_batch(c.p)));
         l.gram[0] = off; off += set;
         l.gram[1] = off; off += set;
         l.gram_perm = off; off += align_up((size_t)kMaxPassesPerLaunch * c.buffer_n * 4);   // second set of partitions
+    }
+    // BMGD_CHAIN_PRODUCT: two sets of scratch for the products of a launch's steps
+    l.prod[0] = l.prod[1] = off;
+    if (c.chain == BMGD_CHAIN_PRODUCT) {
+        const size_t set = align_up(4 * gram_products_scratch_floats(c.p, (int64_t)kMaxPassesPerLaunch * ((c.buffer_n + c.batch_n - 1) / c.batch_n)));
+        l.prod[0] = off; off += set;
+        l.prod[1] = off; off += set;
     }
     // moment matrices kept per buffer index (fixed partitions, cache_moments): n_buffers sets of one pass each
     l.gram_cache = off;
     l.gram_cache_set = 0;
     if (c.cache_moments) {
-        l.gram_cache_set = align_up((size_t)((c.buffer_n + c.batch_n - 1) / c.batch_n) * gram_bytes_per_batch(c.p));
+        l.gram_cache_set = align_up((size_t)((c.buffer_n + c.batch_n - 1) / c.batch_n) *
+                                    (c.chain == BMGD_CHAIN_PRODUCT ? gram_dense_bytes_per_batch(c.p) : gram_bytes_per_batch(c.p)));
         off += l.gram_cache_set * (size_t)c.n_buffers;
+    }
+    // BMGD_CHAIN_PRODUCT with cached moment matrices: per buffer index also the product of a run's steps
+    l.prod_cache = off;
+    l.prod_cache_set = 0;
+    if (c.cache_moments && c.chain == BMGD_CHAIN_PRODUCT) {
+        l.prod_cache_set = align_up(gram_dense_bytes_per_batch(c.p));
+        off += l.prod_cache_set * (size_t)c.n_buffers;
     }
     // optimizer state: like theta; with the redundant reduction every workgroup keeps a private copy (G * p <= 4096
     // words there, rows padded to 16)
@@ -268,6 +299,7 @@ Layout make_layout(const bmgd_config& c)
 int resolve_chain(const bmgd_config& c)
 {
     if (c.model == BMGD_SOFTMAX) return c.chain == BMGD_CHAIN_LAUNCH ? BMGD_CHAIN_LAUNCH : BMGD_CHAIN_GRAPH;
+    if (c.chain == BMGD_CHAIN_PRODUCT) return BMGD_CHAIN_GRAM;      // the moment form with another way through the steps (ctx->products)
     if (c.chain != BMGD_CHAIN_AUTO) return c.chain;
     return gram_eligible(c.model, c.p, c.batch_n) ? BMGD_CHAIN_GRAM : BMGD_CHAIN_PERSISTENT;
 }
@@ -414,6 +446,39 @@ float rate_of(const bmgd_ctx* ctx, int64_t ahead)
     return ctx->lr_tab_host[(size_t)u];
 }
 
+// The steps of a launch in the moment form, on the library's chain stream: the chain of eq. (3.1) step by step, or
+// (BMGD_CHAIN_PRODUCT) the steps multiplied together and applied once.
+hipError_t launch_steps(bmgd_ctx* ctx, const float* set, int64_t rows, int64_t n, int np, int perm_stride, hipEvent_t ev0,
+                        hipEvent_t ev1, bmgd_ctx::CachedMoments* keep = nullptr, uint32_t b = 0)
+{
+    const bmgd_config& c = ctx->cfg;
+    const int lr_len = (int)ctx->lr_tab_host.size();
+    const float* tab = lr_len ? ctx->lr_tab_dev : nullptr;
+    const int lr_base = (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0));
+    if (ctx->products) {
+        // Fixed partitions with cached matrices (keep != null): as long as the rate and the number of passes stay what
+        // they were, the product of a run over buffer index b is the same matrix every time; it is formed once and then
+        // only applied.
+        float* kept = keep && lr_len == 0 ? reinterpret_cast<float*>(ctx->prod_cache + (size_t)b * ctx->lay.prod_cache_set) : nullptr;
+        if (kept && keep->prod_valid && keep->prod_alpha == (float)c.lr && keep->prod_np == np)
+            return gram_launch_apply(kept, ctx->theta, (int)c.p, ctx->chain_stream, ev0, ev1);
+        // (launches on one stream run in order, so the scratch of launch k - 2 is free; two sets alternate anyway, so that
+        // nothing here depends on that)
+        float* scratch = ctx->prod[ctx->psel];
+        ctx->psel ^= 1;
+        hipError_t e = gram_launch_products(set, ctx->theta, scratch, kept, (int)rows, (int)c.p, (int)n, np, perm_stride, (float)c.lr, tab,
+                                            lr_base, lr_len, ctx->chain_stream, ev0, ev1);
+        if (keep) {
+            keep->prod_valid = kept != nullptr && e == hipSuccess;
+            keep->prod_alpha = (float)c.lr;
+            keep->prod_np = np;
+        }
+        return e;
+    }
+    return gram_launch_chain(set, ctx->theta, (int)rows, (int)c.p, (int)n, np, perm_stride, (float)c.lr, tab, lr_base, lr_len,
+                             opt_args(ctx, 0), ctx->chain_stream, ev0, ev1);
+}
+
 // Enqueue passes t = first + 1 .. first + count over (x, y, rows) on `stream`, at most kMaxPassesPerLaunch per launch.
 // *end_event receives the stop event of the last kernel if that kernel carries one (and then runs on the
 // library's chain stream), else NULL: then the passes end with the last work enqueued on `stream`.
@@ -457,16 +522,15 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
                 if (ce.valid) HIP_TRY(ctx, hipStreamWaitEvent(stream, ctx->cache_chain_done, 0));
                 HIP_TRY(ctx, launch_perm(ctx->gram_perm[0], rows, 1, keys, stream));
                 HIP_TRY(ctx, gram_launch_moments(static_cast<const float*>(x), static_cast<const float*>(y), ctx->gram_perm[0], set,
-                                                 (int)rows, (int)c.p, (int)n, np, 0, stream, pv0, pv1));
+                                                 (int)rows, (int)c.p, (int)n, np, 0, stream, pv0, pv1, ctx->products));
                 HIP_TRY(ctx, hipEventRecord(ce.ready, stream));
                 ce.valid = true;
+                ce.prod_valid = false;
                 ce.rows = rows;
             }
             HIP_TRY(ctx, hipStreamWaitEvent(ctx->chain_stream, ce.ready, 0));
-            HIP_TRY(ctx, gram_launch_chain(set, ctx->theta, (int)rows, (int)c.p, (int)n, np, 0, (float)c.lr,
-                                           lr_len ? ctx->lr_tab_dev : nullptr,
-                                           (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0)), lr_len, opt_args(ctx, 0),
-                                           ctx->chain_stream, ev0, ev1));
+            // (the product of a whole run can be kept: one launch must cover the run)
+            HIP_TRY(ctx, launch_steps(ctx, set, rows, n, np, 0, ev0, ev1, count == np ? &ce : nullptr, b));
             if (!ctx->cache_chain_done) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->cache_chain_done, hipEventDisableTiming));
             HIP_TRY(ctx, hipEventRecord(ctx->cache_chain_done, ctx->chain_stream));
             ctx->lr_pos += (int64_t)np * M;
@@ -487,14 +551,11 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
             HIP_TRY(ctx, launch_perm(ctx->gram_perm[i], rows, nperm, keys, stream, ctx->subset, ctx->subset_limit, ctx->sync + 2));
             HIP_TRY(ctx, gram_launch_moments(static_cast<const float*>(x), static_cast<const float*>(y), ctx->gram_perm[i],
                                              ctx->gram[i], (int)rows, (int)c.p, (int)n, np, fixed ? 0 : (int)rows, stream,
-                                             pv0, pv1));
+                                             pv0, pv1, ctx->products));
             ctx->prep_done[i] = pv1;
             HIP_TRY(ctx, hipStreamWaitEvent(ctx->chain_stream, ctx->prep_done[i], 0));
             // the timing events are completed by the chain's dispatch; the stop event also frees set i
-            HIP_TRY(ctx, gram_launch_chain(ctx->gram[i], ctx->theta, (int)rows, (int)c.p, (int)n, np, fixed ? 0 : (int)rows,
-                                           (float)c.lr, lr_len ? ctx->lr_tab_dev : nullptr,
-                                           (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0)), lr_len, opt_args(ctx, 0),
-                                           ctx->chain_stream, ev0, ev1));
+            HIP_TRY(ctx, launch_steps(ctx, ctx->gram[i], rows, n, np, fixed ? 0 : (int)rows, ev0, ev1));
             ctx->lr_pos += (int64_t)np * M;
             ctx->opt_k += (int64_t)np * M;
             ctx->chain_done[i] = ev1;                // stays valid until the records are settled, after a drain
@@ -801,7 +862,11 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->xt = base + ctx->lay.xt;
     ctx->gram[0] = reinterpret_cast<float*>(base + ctx->lay.gram[0]);
     ctx->gram[1] = reinterpret_cast<float*>(base + ctx->lay.gram[1]);
+    ctx->prod[0] = reinterpret_cast<float*>(base + ctx->lay.prod[0]);
+    ctx->prod[1] = reinterpret_cast<float*>(base + ctx->lay.prod[1]);
+    ctx->products = cfg->chain == BMGD_CHAIN_PRODUCT;
     ctx->gram_cache = base + ctx->lay.gram_cache;
+    ctx->prod_cache = base + ctx->lay.prod_cache;
     if (cfg->cache_moments) ctx->mcache.resize((size_t)cfg->n_buffers);
     ctx->gram_perm[0] = ctx->perm;
     ctx->gram_perm[1] = reinterpret_cast<int32_t*>(base + ctx->lay.gram_perm);
@@ -1117,7 +1182,7 @@ BMGD_API int bmgd_clear_moment_cache(bmgd_ctx* ctx)
     if (!ctx) return BMGD_EINVAL;
     const int rc = drain(ctx);                           // no chain may still be reading them
     if (rc != BMGD_OK) return rc;
-    for (auto& ce : ctx->mcache) ce.valid = false;
+    for (auto& ce : ctx->mcache) ce.valid = ce.prod_valid = false;
     return BMGD_OK;
 }
 
@@ -1345,7 +1410,7 @@ BMGD_API int bmgd_get_stats(bmgd_ctx* ctx, bmgd_stats* out)
     out->n_workgroups = one_group ? 1 : ctx->shape.G;
     out->threads_per_group = one_group ? gram_chain_threads(ctx->cfg.p)
                              : ctx->chain == BMGD_CHAIN_PERSISTENT ? ctx->shape.chain_block : ctx->shape.block;
-    out->chain = ctx->chain;
+    out->chain = ctx->products ? BMGD_CHAIN_PRODUCT : ctx->chain;
     out->chain_ms = ctx->chain_ms;
     out->chain_launches = ctx->chain_launches;
     out->prep_ms = ctx->prep_ms;

@@ -172,12 +172,26 @@ int gram_chain_threads(int64_t p);
 // Moment matrices of all mini-batches of `npass` passes (partitions at perm + pass * perm_stride) into `gram`.
 // `start` and `stop` (each may be NULL) are completed by the kernel's own dispatch, here and below.
 hipError_t gram_launch_moments(const float* X, const float* y, const int32_t* perm, float* gram, int rows, int p, int n, int npass,
-                               int perm_stride, hipStream_t stream, hipEvent_t start, hipEvent_t stop);
+                               int perm_stride, hipStream_t stream, hipEvent_t start, hipEvent_t stop, bool dense = false);
+// dense = true: each mini-batch's [Sxx_m | -Sxy_m] as a dense row-major matrix of order gram_dense_order(p) (p + 1 rounded
+// up to 16; what lies beyond row p - 1 or column p is never written and must be zero), for gram_launch_products
+int gram_dense_order(int64_t p);
+size_t gram_dense_bytes_per_batch(int64_t p);
 // The npass * ceil(rows / n) updates of theta from those matrices, in one workgroup.
 // lr_tab (may be NULL): learning rate of step s is lr_tab[min(lr_base + s, lr_len - 1)] instead of alpha.
 hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, int n, int npass, int perm_stride, float alpha,
                              const float* lr_tab, int lr_base, int lr_len, const OptArgs& opt, hipStream_t stream,
                              hipEvent_t start, hipEvent_t stop);
+// BMGD_CHAIN_PRODUCT (gram_products.hip): the npass * M steps of a launch as affine maps, multiplied together pairwise
+// in log2 rounds and applied to theta once.  `gram`: the dense matrices of gram_launch_moments(..., dense = true).
+// `scratch`: gram_products_scratch_floats(p, npass * M) floats.  Plain steps only.
+size_t gram_products_scratch_floats(int64_t p, int64_t max_steps);
+hipError_t gram_launch_products(const float* gram, float* theta, float* scratch, float* product_out, int rows, int p, int n, int npass,
+                                int perm_stride, float alpha, const float* lr_tab, int lr_base, int lr_len, hipStream_t stream,
+                                hipEvent_t start, hipEvent_t stop);
+// product_out (optional): where the product of the launch's steps is left, gram_dense_order(p)^2 floats; gram_launch_apply
+// applies such a product to theta again (fixed partitions, constant rate: the product of a buffer is the same every time)
+hipError_t gram_launch_apply(const float* product, float* theta, int p, hipStream_t stream, hipEvent_t start, hipEvent_t stop);
 
 // ---------------------------------------------------------------------------------------------------
 // Softmax regression (bf16 predictors, fp32 master weights) on the matrix cores.

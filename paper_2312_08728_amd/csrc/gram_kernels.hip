@@ -8,6 +8,7 @@
 // then costs p^2 multiply-adds and 4 p^2 bytes per step inside ONE workgroup: no exchange between workgroups
 // at all.  Same arithmetic as the row form up to the order of summation.
 #include "bmgd_internal.h"
+#include "gram_layout.h"
 
 #include <hip/hip_ext.h>
 
@@ -24,26 +25,6 @@ __device__ __forceinline__ float dpp_mov(float v)
 {
     return __builtin_bit_cast(float,
                               __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-
-// Where the chain kernel wants entry (r, c) of Sxx_m: thread t = r * tpr + seg of the chain owns, of row r, the
-// float4 chunks seg + tpr k (k < kq) and the single columns 4 tpr kq + tpr j + seg (j < ks); all threads' k-th
-// chunks are contiguous ("plane" k), so every load instruction of a wavefront reads one contiguous KiB.
-struct GramLayout {
-    int p, tpr, nthr, kq, ks;
-    int b_off;          // Sxy_m: p floats
-    int step_floats;    // floats per mini-batch, multiple of 4
-};
-
-__device__ __host__ __forceinline__ int gram_pos(const GramLayout& L, int r, int c)
-{
-    const int wide = 4 * L.tpr * L.kq;
-    if (c < wide) {
-        const int chunk = c >> 2, k = chunk / L.tpr, seg = chunk % L.tpr;
-        return ((k * L.nthr + r * L.tpr + seg) << 2) + (c & 3);
-    }
-    const int cc = c - wide, j = cc / L.tpr, seg = cc % L.tpr;
-    return 4 * L.kq * L.nthr + j * L.nthr + r * L.tpr + seg;
 }
 
 struct GramTiles {
@@ -63,7 +44,7 @@ template <int TPW, bool WIDE>
 __global__ void __launch_bounds__(64 * kGramWaves) gram_mfma_kernel(const float* __restrict__ X, const float* __restrict__ y,
                                                                      const int* __restrict__ perm, float* __restrict__ out,
                                                                      int rows, int n, int perm_stride, int M, int n_items,
-                                                                     int stride, GramLayout L, GramTiles T)
+                                                                     int stride, GramLayout L, GramTiles T, int dense_q)
 {
     extern __shared__ __align__(16) float lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -151,7 +132,9 @@ __global__ void __launch_bounds__(64 * kGramWaves) gram_mfma_kernel(const float*
     for (int t = 0; t < TPW; ++t) red[(wave * TPW + t) * 64 + lane] = acc[t];
     __syncthreads();
     const float inv = 1.f / (float)nb;
-    float* o = out + (size_t)(pass * M + m) * L.step_floats;
+    // dense_q > 0: the matrix [Sxx_m | -Sxy_m] goes out dense, row-major with row stride dense_q, for the kernel that
+    // multiplies steps together (gram_products.hip); rows and columns beyond it are never written (they stay zero)
+    float* o = out + (size_t)(pass * M + m) * (dense_q > 0 ? (size_t)dense_q * dense_q : (size_t)L.step_floats);
     const int my_tiles = min(TPW, T.ntiles - part * TPW);
     for (int t = wave; t < my_tiles; t += kGramWaves) {
         floatx4 s = red[t * 64 + lane];
@@ -164,7 +147,14 @@ __global__ void __launch_bounds__(64 * kGramWaves) gram_mfma_kernel(const float*
         for (int q = 0; q < 4; ++q) {
             const int r = I + 4 * (lane >> 4) + q;
             const float val = s[q] * inv;
-            if (r < p && c < p) {
+            if (dense_q > 0) {
+                if (r < p && c < p) {
+                    o[r * dense_q + c] = val;
+                    if (I != J) o[c * dense_q + r] = val;
+                } else if (r < p && c == p) {
+                    o[r * dense_q + p] = -val;
+                }
+            } else if (r < p && c < p) {
                 o[gram_pos(L, r, c)] = val;
                 if (I != J) o[gram_pos(L, c, r)] = val;
             } else if (r < p && c == p) {
@@ -281,20 +271,6 @@ __global__ void __launch_bounds__(1024) gram_chain_kernel(const float* __restric
     }
 }
 
-GramLayout make_layout(int p)
-{
-    GramLayout L{};
-    L.p = p;
-    L.tpr = p <= 64 ? 16 : 8;
-    L.nthr = (p * L.tpr + 63) / 64 * 64;
-    L.kq = p / (4 * L.tpr);
-    const int rem = p - 4 * L.tpr * L.kq;
-    L.ks = (rem + L.tpr - 1) / L.tpr;
-    L.b_off = 4 * L.kq * L.nthr + L.ks * L.nthr;
-    L.step_floats = (L.b_off + p + 3) & ~3;
-    return L;
-}
-
 // tiles per workgroup for NT tile rows: {few workgroups, many workgroups}
 void tile_split(int ntiles, int wgs_per_split, int* tsplit, int* tpw)
 {
@@ -315,15 +291,15 @@ void tile_split(int ntiles, int wgs_per_split, int* tsplit, int* tpw)
 template <int TPW>
 hipError_t launch_gram_mfma(bool wide, dim3 grid, size_t lds, hipStream_t stream, const float* X, const float* y, const int32_t* perm,
                             float* out, int rows, int n, int perm_stride, int M, int n_items, int stride, const GramLayout& L,
-                            const GramTiles& T, hipEvent_t start, hipEvent_t stop)
+                            const GramTiles& T, int dense_q, hipEvent_t start, hipEvent_t stop)
 {
     // the events ride on the dispatch itself: no separate markers in the queue
     if (wide)
         hipExtLaunchKernelGGL((gram_mfma_kernel<TPW, true>), grid, dim3(64 * kGramWaves), (uint32_t)lds, stream, start, stop, 0u, X,
-                              y, perm, out, rows, n, perm_stride, M, n_items, stride, L, T);
+                              y, perm, out, rows, n, perm_stride, M, n_items, stride, L, T, dense_q);
     else
         hipExtLaunchKernelGGL((gram_mfma_kernel<TPW, false>), grid, dim3(64 * kGramWaves), (uint32_t)lds, stream, start, stop, 0u, X,
-                              y, perm, out, rows, n, perm_stride, M, n_items, stride, L, T);
+                              y, perm, out, rows, n, perm_stride, M, n_items, stride, L, T, dense_q);
     return hipGetLastError();
 }
 
@@ -372,14 +348,23 @@ size_t gram_bytes_per_batch(int64_t p)
     return (size_t)make_layout((int)p).step_floats * sizeof(float);
 }
 
+int gram_dense_order(int64_t p) { return (int)((p + 1 + 15) / 16 * 16); }
+
+size_t gram_dense_bytes_per_batch(int64_t p)
+{
+    const size_t q = (size_t)gram_dense_order(p);
+    return q * q * sizeof(float);
+}
+
 int gram_chain_threads(int64_t p)
 {
     return make_layout((int)p).nthr;
 }
 
 hipError_t gram_launch_moments(const float* X, const float* y, const int32_t* perm, float* gram, int rows, int p, int n, int npass,
-                               int perm_stride, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
+                               int perm_stride, hipStream_t stream, hipEvent_t start, hipEvent_t stop, bool dense)
 {
+    const int dense_q = dense ? gram_dense_order(p) : 0;
     if (p < 1 || p > kGramMaxP) return hipErrorInvalidValue;
     const GramLayout L = make_layout(p);
     const int M = (rows + n - 1) / n;
@@ -403,7 +388,7 @@ hipError_t gram_launch_moments(const float* X, const float* y, const int32_t* pe
     const dim3 grid((unsigned)((n_items + 7) / 8 * 8 * T.tsplit));
     const bool wide = p > 64;
     hipError_t e = hipErrorInvalidValue;
-#define GRAM_CASE(N) case N: e = launch_gram_mfma<N>(wide, grid, lds, stream, X, y, perm, gram, rows, n, perm_stride, M, n_items, stride, L, T, start, stop); break
+#define GRAM_CASE(N) case N: e = launch_gram_mfma<N>(wide, grid, lds, stream, X, y, perm, gram, rows, n, perm_stride, M, n_items, stride, L, T, dense_q, start, stop); break
     switch (tpw) {
         GRAM_CASE(1); GRAM_CASE(3); GRAM_CASE(5); GRAM_CASE(6); GRAM_CASE(7); GRAM_CASE(9); GRAM_CASE(10);
     }

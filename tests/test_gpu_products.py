@@ -1,0 +1,113 @@
+"""BMGD_CHAIN_PRODUCT: the steps of a launch as affine maps, multiplied together (the products of eq. (3.2)) and applied
+once.  Parity against the oracle, which applies eq. (2.1) step by step in fp64."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_util import gpu_run, oracle_run, rel_l2
+from oracle import bmgd as O
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def _case(N, p, N0, n, T, R, alpha):
+    return wl.CONFIGS["cfg2"].scaled(name="case", N=N, p=p, N0=N0, n=n, T=T, R=R, alpha=alpha)
+
+
+@pytest.mark.parametrize("p,N0,n,T,reshuffle", [
+    (24, 3000, 200, 3, 0),          # 45 steps per launch: rounds of 23, 12, 6, 3, 2, 1 (odd counts carry a factor over)
+    (100, 20000, 1000, 3, 0),       # cfg2's shape: 60 steps per launch, matrices of order 112
+    (128, 4000, 300, 2, 0),         # the largest p (order 144, nine tile columns), a short last mini-batch
+    (10, 2000, 2000, 1, 0),         # a single step per launch: nothing to multiply
+    (7, 1500, 100, 5, 0),           # more passes than one launch holds (4 + 1), odd p
+    (40, 4000, 250, 3, 1),          # fixed partitions: every pass multiplies the same matrices
+])
+def test_products_against_the_oracle(p, N0, n, T, reshuffle):
+    import paper_2312_08728_amd as B
+    w = _case(2 * N0, p, N0, n, T, 2, 0.02)
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y, reshuffle=O.FIXED if reshuffle else O.PER_PASS)
+    got, st = gpu_run(w, X, y, chain=B.BMGD_CHAIN_PRODUCT, reshuffle=reshuffle)
+    M = -(-N0 // n)
+    assert st.chain == B.BMGD_CHAIN_PRODUCT and st.steps == 2 * 2 * T * M
+    assert rel_l2(got, want) <= TOL
+    # and the step-by-step chain on the same moment matrices gives the same estimate up to fp32 rounding
+    chain, _ = gpu_run(w, X, y, chain=B.BMGD_CHAIN_GRAM, reshuffle=reshuffle)
+    assert rel_l2(got, chain) <= 1e-5
+
+
+def test_products_with_a_learning_rate_per_update():
+    import torch
+    import paper_2312_08728_amd as B
+    w = _case(6000, 24, 3000, 200, 3, 1, 0.02)
+    X, y = wl.dataset(w)
+    M = 15
+    sched = (0.02 * (0.5 + 0.5 * np.cos(np.pi * np.arange(2 * 3 * M) / (2 * 3 * M)))).astype(np.float32)
+    ref = O.BMGD(w.model, w.p, w.n, w.alpha, w.T)
+    ref.set_lr_schedule(sched)
+    ref.run_buffer(X[:3000], y[:3000])
+    ref.run_buffer(X[3000:], y[3000:])
+    ctx = B.Context(w.p, w.N0, w.n, w.alpha, w.T, chain=B.BMGD_CHAIN_PRODUCT)
+    ctx.set_lr_schedule(sched)
+    xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    s = torch.cuda.Stream()
+    ctx.run_device_buffer(xd[:3000], yd[:3000], 3000, s)
+    ctx.run_device_buffer(xd[3000:], yd[3000:], 3000, s)
+    assert rel_l2(ctx.get_theta(), ref.theta) <= TOL
+    ctx.close()
+
+
+def test_products_refuse_what_they_cannot_do():
+    import paper_2312_08728_amd as B
+    for kw in (dict(optimizer=B.BMGD_OPT_ADAM), dict(model=wl.LOGISTIC)):
+        with pytest.raises(B.BmgdError) as e:
+            B.Context(24, 3000, 200, 0.02, 3, chain=B.BMGD_CHAIN_PRODUCT, **kw)
+        assert e.value.code == B.BMGD_EINVAL
+    with pytest.raises(B.BmgdError) as e:                             # p above the moment form's limit
+        B.Context(136, 3000, 300, 0.02, 3, chain=B.BMGD_CHAIN_PRODUCT)
+    assert e.value.code == B.BMGD_EINVAL
+    with pytest.raises(B.BmgdError) as e:                             # scratch for 4 * 10^5 steps of order 112: far too much
+        B.Context(100, 1_000_000, 10, 0.02, 3, chain=B.BMGD_CHAIN_PRODUCT)
+    assert e.value.code == B.BMGD_EINVAL
+
+
+def test_products_over_cached_moment_matrices():
+    """Fixed partitions with the moment matrices of every buffer kept on the device: iterations after the first read no
+    row, and while the learning rate and the number of passes stay the same the product of a buffer's steps is kept too
+    and only applied.  Same estimate, bit for bit, as without the cache; a new learning rate makes new products."""
+    import torch
+    import paper_2312_08728_amd as B
+    w = _case(8000, 40, 4000, 250, 3, 3, 0.02)
+    X, y = wl.dataset(w)
+    want = oracle_run(w, X, y, reshuffle=O.FIXED)
+    xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    s = torch.cuda.Stream()
+    plain = B.Context(w.p, w.N0, w.n, w.alpha, w.T, chain=B.BMGD_CHAIN_PRODUCT, reshuffle=B.BMGD_RESHUFFLE_FIXED, n_buffers=2)
+    ctx = B.Context(w.p, w.N0, w.n, w.alpha, w.T, chain=B.BMGD_CHAIN_PRODUCT, reshuffle=B.BMGD_RESHUFFLE_FIXED, n_buffers=2,
+                    cache_moments=True)
+    def sweep(c, cached):
+        for k in range(2):
+            if cached:
+                c.run_cached_buffer(s)
+            else:
+                c.run_device_buffer(xd[k * 4000:(k + 1) * 4000], yd[k * 4000:(k + 1) * 4000], 4000, s)
+    sweep(ctx, False)
+    sweep(ctx, True)
+    sweep(ctx, True)
+    for _ in range(3):
+        sweep(plain, False)
+    got = ctx.get_theta()
+    assert np.array_equal(got, plain.get_theta())
+    assert rel_l2(got, want) <= TOL
+    assert ctx.stats().steps == 3 * 2 * 3 * 16
+    for c in (ctx, plain):
+        c.set_lr(0.01)
+    sweep(ctx, True)
+    sweep(ctx, True)
+    sweep(plain, False)
+    sweep(plain, False)
+    assert np.array_equal(ctx.get_theta(), plain.get_theta())
+    ctx.close()
+    plain.close()
