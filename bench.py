@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM traffic of one launch of the chain kernel on the primary workload, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE (see profiles/), scaled by the copy calibration; valid only for the source of the kernel it was measured on
 # (the line reports null once that file has changed: measure again and update the entry).
-TRAFFIC = {"cfg3": {"sources": ('glm_narrow_kernel.hip', 'glm_exchange.h', 'glm_device.h'), "kernel_sha256": "45fef1bf3ccf41c027138800dba42d12c1e5535d30ae6f2492f523b280ed68fe", "bytes_per_launch": 2473478069}, "cfg4": {"sources": ("glm_split_kernel.hip",), "kernel_sha256": "26aae02c8ac2ca4a3de45e88fc878a39d6a76f25ad58578c3026c20aa59d4ded", "bytes_per_launch": 9433322236}}
+TRAFFIC = {"cfg2": {"sources": ('gram_kernels.hip', 'gram_layout.h'), "kernel_sha256": "5fb88e9240e37f4f3e315a7cbd717429f81daa0626c33f61a63fb93afe49612d", "bytes_per_launch": 178928796}, "cfg3": {"sources": ('glm_narrow_kernel.hip', 'glm_exchange.h', 'glm_device.h'), "kernel_sha256": "45fef1bf3ccf41c027138800dba42d12c1e5535d30ae6f2492f523b280ed68fe", "bytes_per_launch": 2473478069}, "cfg4": {"sources": ('glm_split_kernel.hip', 'glm_exchange.h', 'glm_device.h'), "kernel_sha256": "8d8c2fd79cd5ea4e1c2d85d65948ba501b3f0dcb49b443ac8ecd2b5b9677dfeb", "bytes_per_launch": 9428150173}}
 
 
 def _kernel_sha(sources) -> str:
