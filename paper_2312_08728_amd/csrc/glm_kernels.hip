@@ -221,7 +221,8 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
     const int iters_full = (a.n + S_total * PF - 1) / (S_total * PF);
     const int iters_tail = (n_tail + S_total * PF - 1) / (S_total * PF);
     auto batch_rows = [&](int s) { int t, m; split(s, t, m); return m == M - 1 ? n_tail : a.n; };
-    auto batch_base = [&](int s) { int t, m; split(s, t, m); return t * a.perm_stride + m * a.n; };
+    // (in 64 bits: up to four partitions of up to 2^30 rows lie behind one another)
+    auto batch_base = [&](int s) { int t, m; split(s, t, m); return (size_t)t * (size_t)a.perm_stride + (size_t)m * (size_t)a.n; };
     auto batch_iters = [&](int s) { int t, m; split(s, t, m); return m == M - 1 ? iters_tail : iters_full; };
 
     // Row indices of group (s, it) for this lane's row slot; -1 where the slot has no row.
@@ -231,13 +232,14 @@ __global__ void __launch_bounds__(BLOCK) glm_chain_kernel(GlmArgs a)
     auto load_idx = [&](int s, int it, int (&idx)[PF]) {
         const bool live = s < last;
         const int sc = live ? s : first;
-        const int nb = batch_rows(sc), base = batch_base(sc);
+        const int nb = batch_rows(sc);
+        const size_t base = batch_base(sc);
         okn = 0u;
 #pragma unroll
         for (int q = 0; q < PF; ++q) {
             const int j = (it * PF + q) * S_total + myslot;
             const bool ok = live && j < nb;
-            idx[q] = a.perm[base + (ok ? j : 0)];
+            idx[q] = a.perm[base + (size_t)(ok ? j : 0)];
             okn |= ok ? (1u << q) : 0u;
         }
     };
