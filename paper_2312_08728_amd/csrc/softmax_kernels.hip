@@ -106,10 +106,14 @@ struct GemmArgs {
 // LDS buffers, and one is being multiplied.  A tile's arithmetic takes ~0.1 us while a trip to L2/HBM takes
 // ~1 us, so the loop would otherwise run at memory latency.
 constexpr int kDepth = 4;
+// Eight wavefronts per workgroup, two per SIMD, each with a 64 x 32 part of the 128 x 128 tile: a wavefront's waits (global ->
+// register -> shared memory -> register -> MFMA) are covered by its SIMD mate.
+constexpr int kGemmThreads = 512;
+constexpr int kWN = 32;                             // columns of the tile per wavefront (one MFMA tile wide, two high)
 
 // OPT (with UPDATE): an update rule other than the plain step, in an instantiation of its own.
 template <bool UPDATE, bool OPT = false>
-__global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
+__global__ void __launch_bounds__(kGemmThreads) gemm_nt_kernel(GemmArgs g)
 {
     __shared__ __align__(16) unsigned short As[2][TM * LDS_STRIDE];
     __shared__ __align__(16) unsigned short Bs[2][TN * LDS_STRIDE];
@@ -130,16 +134,17 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
     const int ke = min(g.K, kb + g.k_per_split);
     const int ntiles = (ke - kb + TK - 1) / TK;
 
-    // Each thread moves two 16-byte chunks of A and two of B per K tile.  Every request is unconditional, from a
+    // Each thread moves one 16-byte chunk of A and one of B per K tile.  Every request is unconditional, from a
     // clamped row and a clamped K offset; what lies outside the operands is zeroed when the chunk goes to LDS.
     // (A branch or a select next to the load would make the compiler wait for the load on the spot.)
-    const unsigned short* a_ptr[2];
-    const unsigned short* b_ptr[2];
-    int lds_off[2], kc[2];
-    bool a_ok[2], b_ok[2];
+    constexpr int CPT = TM * (TK / 8) / kGemmThreads;   // chunks per thread and operand
+    const unsigned short* a_ptr[CPT];
+    const unsigned short* b_ptr[CPT];
+    int lds_off[CPT], kc[CPT];
+    bool a_ok[CPT], b_ok[CPT];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int chunk = tid + h * 256;
+    for (int h = 0; h < CPT; ++h) {
+        const int chunk = tid + h * kGemmThreads;
         const int row = chunk >> 2;
         kc[h] = (chunk & 3) * 8;
         lds_off[h] = row * LDS_STRIDE + kc[h];
@@ -151,10 +156,10 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
         b_ptr[h] = g.B + (size_t)bnc * g.b_stride;
     }
     const int klast = g.K - 8;                       // K is a multiple of 8
-    auto fetch = [&](int tile_k, uint4 (&ra)[2], uint4 (&rb)[2]) {
+    auto fetch = [&](int tile_k, uint4 (&ra)[CPT], uint4 (&rb)[CPT]) {
         const int k0 = kb + tile_k * TK;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < CPT; ++h) {
             const int k = min(k0 + kc[h], klast);
             ra[h] = *reinterpret_cast<const uint4*>(a_ptr[h] + k);
             rb[h] = *reinterpret_cast<const uint4*>(b_ptr[h] + k);
@@ -162,22 +167,24 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
     };
     auto masked = [](uint4 v, bool ok) { return ok ? v : make_uint4(0, 0, 0, 0); };
 
-    f32x16 acc[2][2];
+    constexpr int NJ = kWN / 32;                     // MFMA tiles side by side per wavefront
+    f32x16 acc[2][NJ];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    constexpr int WCOLS = TN / kWN;                  // wavefronts side by side
+    const int wm = (wave / WCOLS) * 64, wn = (wave % WCOLS) * kWN;
     const int frow = lane & 31, fk = (lane >> 5) * 8;
 
     // Ring of kDepth register slots.  A slot goes to LDS, and only then is requested again, so no copy of it is
     // ever live across a request; the first requests are waited for before the loop (the compiler is free to
     // reorder them) so that the waits inside the loop count the loop's own requests, oldest slot first.  The
     // loop has no branch: tiles past the last one are all zeros and add nothing.
-    uint4 ra[kDepth][2], rb[kDepth][2];
+    uint4 ra[kDepth][CPT], rb[kDepth][CPT];
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) fetch(d, ra[d], rb[d]);
     __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
@@ -188,7 +195,7 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
             const int buf = d & 1;                   // kDepth is even, so tile t uses buffer t % 2
             const int k0 = kb + t * TK;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < CPT; ++h) {
                 const bool kin = k0 + kc[h] < ke;
                 *reinterpret_cast<uint4*>(&As[buf][lds_off[h]]) = masked(ra[d][h], a_ok[h] && kin);
                 *reinterpret_cast<uint4*>(&Bs[buf][lds_off[h]]) = masked(rb[d][h], b_ok[h] && kin);
@@ -197,16 +204,17 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
             __syncthreads();                         // tile t visible; the other buffer was last read before this point
 #pragma unroll
             for (int ks = 0; ks < TK; ks += 16) {
-                bf16x8 fa[2], fb[2];
+                bf16x8 fa[2], fb[NJ];
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
+                for (int i = 0; i < 2; ++i)
                     fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[buf][(wm + i * 32 + frow) * LDS_STRIDE + ks + fk]));
-                    fb[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[buf][(wn + i * 32 + frow) * LDS_STRIDE + ks + fk]));
-                }
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    fb[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[buf][(wn + j * 32 + frow) * LDS_STRIDE + ks + fk]));
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+                    for (int j = 0; j < NJ; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
             }
         }
@@ -220,7 +228,7 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int r = m0 + wm + i * 32 + 8 * (v >> 2) + rbase + (v & 3);
@@ -237,9 +245,9 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
         // branch, and only then combined and stored (a branch around each load would wait for it on the spot).
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            float wv[2][16];
+            float wv[NJ][16];
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int r = min(m0 + wm + i * 32 + 8 * (v >> 2) + rbase + (v & 3), g.M - 1);
@@ -247,7 +255,7 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
                     wv[j][v] = g.W[(size_t)r * g.ldw + c];
                 }
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int lr = wm + i * 32 + 8 * (v >> 2) + rbase + (v & 3);
@@ -271,7 +279,7 @@ __global__ void __launch_bounds__(256) gemm_nt_kernel(GemmArgs g)
         }
         __syncthreads();
         // 128 class rows x 128 features: 16 chunks of 8 features per class row
-        for (int chunk = tid; chunk < TN * (TM / 8); chunk += 256) {
+        for (int chunk = tid; chunk < TN * (TM / 8); chunk += kGemmThreads) {
             const int lc = chunk >> 4, lr = (chunk & 15) * 8;
             const int c = n0 + lc, r = m0 + lr;
             if (c < g.ldw && r < g.ldwt)
@@ -537,7 +545,7 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
     g.tiles_m = (s.nb + TM - 1) / TM;
     g.tiles_n = d.c_pad / TN;
     g.splits = d.splits;
-    hipLaunchKernelGGL(gemm_nt_kernel<false>, dim3((g.tiles_m * g.tiles_n * g.splits + 7) / 8 * 8), dim3(256), 0, stream, g);
+    hipLaunchKernelGGL(gemm_nt_kernel<false>, dim3((g.tiles_m * g.tiles_n * g.splits + 7) / 8 * 8), dim3(kGemmThreads), 0, stream, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // 2. residual
@@ -568,9 +576,9 @@ hipError_t softmax_step(const SoftmaxStep& s, const SoftmaxDims& d, hipStream_t 
     h.tiles_n = d.c_pad / TN;
     h.splits = 1;
     if (s.opt.kind != kOptSgd)
-        hipLaunchKernelGGL((gemm_nt_kernel<true, true>), dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(256), 0, stream, h);
+        hipLaunchKernelGGL((gemm_nt_kernel<true, true>), dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(kGemmThreads), 0, stream, h);
     else
-        hipLaunchKernelGGL((gemm_nt_kernel<true, false>), dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(256), 0, stream, h);
+        hipLaunchKernelGGL((gemm_nt_kernel<true, false>), dim3((h.tiles_m * h.tiles_n + 7) / 8 * 8), dim3(kGemmThreads), 0, stream, h);
     return hipGetLastError();
 }
 
@@ -593,7 +601,7 @@ hipError_t softmax_launch_loss(const void* X, const int32_t* y, int nb, int p, i
     g.tiles_m = (nb + TM - 1) / TM;
     g.tiles_n = d.c_pad / TN;
     g.splits = d.splits;
-    hipLaunchKernelGGL(gemm_nt_kernel<false>, dim3((g.tiles_m * g.tiles_n * g.splits + 7) / 8 * 8), dim3(256), 0, stream, g);
+    hipLaunchKernelGGL(gemm_nt_kernel<false>, dim3((g.tiles_m * g.tiles_n * g.splits + 7) / 8 * 8), dim3(kGemmThreads), 0, stream, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(softmax_loss_kernel, dim3((nb + SM_ROWS - 1) / SM_ROWS), dim3(SM_THREADS), 0, stream, U, d.splits, d.m_pad,
