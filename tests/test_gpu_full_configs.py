@@ -1,8 +1,8 @@
 """Parity at the full size of the five run configurations, in the launch configuration bench.py times (same p,
 buffer size, mini-batch size, passes, learning rate, automatic workgroup count).
 
-cfg1, cfg2 and cfg3 run whole (R * K buffers).  cfg4 and cfg5 run a declared prefix of their run at full buffer
-size (the test names say which); their whole runs are the same tests with BMGD_SLOW=1.  The estimate is compared
+All five run whole (R * K buffer runs at full buffer size; cfg4 and cfg5 together take about two and a half minutes,
+most of it the oracle; BMGD_QUICK=1 cuts them to their first 4 and 2 buffer runs).  The estimate is compared
 with the oracle after EVERY buffer, by relative L2 error (the stated metric) and by the largest error of a single
 coordinate relative to the largest coordinate.  The short-buffer cases at the end are the quick tier."""
 import os
@@ -15,7 +15,7 @@ from gpu_util import gpu_run, oracle_run, parity_after_every_buffer, rel_l2
 
 pytestmark = pytest.mark.gpu
 
-SLOW = os.environ.get("BMGD_SLOW", "") == "1"
+QUICK = os.environ.get("BMGD_QUICK", "") == "1"
 TOL_F32 = 1e-4           # fp32 least squares / logistic paths
 TOL_BF16 = 2e-3          # softmax: bf16 operands, fp32 accumulation and master weights
 
@@ -54,24 +54,23 @@ def test_cfg3_whole_run_theta_after_every_buffer():
     assert max(e[0] for e in errs) <= TOL_F32 and max(e[1] for e in errs) <= TOL_F32
 
 
-def test_cfg4_first_four_full_buffers_theta_after_every_buffer():
-    """Least squares with p = 4096: the first 4 of the run's 16 buffer runs (BMGD_SLOW=1: all 16), each a full
-    250,000 x 4,096 buffer (4.1 GB slot) through the pinned-host loader, both passes, M = 31 with the ragged
-    last mini-batch of 4,240 rows: 248 of 992 updates."""
+def test_cfg4_whole_run_theta_after_every_buffer():
+    """Least squares with p = 4096: all 16 buffer runs (BMGD_QUICK=1: the first 4), each a full 250,000 x 4,096 buffer
+    (4.1 GB slot) through the pinned-host loader, both passes, M = 31 with the ragged last mini-batch of 4,240 rows:
+    992 updates."""
     w = wl.CONFIGS["cfg4"]
-    runs = w.R * w.K if SLOW else 4
+    runs = 4 if QUICK else w.R * w.K
     errs, st = parity_after_every_buffer(w, runs, report=_report("cfg4"))
     assert st.steps == runs * 62 and st.n_workgroups == 256 and st.threads_per_group == 704
     assert st.h2d_bytes == runs * w.N0 * (w.p + 1) * 4
     assert max(e[0] for e in errs) <= TOL_F32 and max(e[1] for e in errs) <= TOL_F32
 
 
-def test_cfg5_first_two_full_buffers_theta_after_every_buffer():
-    """Softmax regression, 3,072 features x 1,000 classes: the first 2 of the run's 20 buffer runs (BMGD_SLOW=1: all
-    20), each a full buffer of 100,000 bf16 rows, both passes, M = 98 with the ragged last mini-batch of 672 rows:
-    392 of 3,920 updates."""
+def test_cfg5_whole_run_theta_after_every_buffer():
+    """Softmax regression, 3,072 features x 1,000 classes: all 20 buffer runs (BMGD_QUICK=1: the first 2), each a full
+    buffer of 100,000 bf16 rows, both passes, M = 98 with the ragged last mini-batch of 672 rows: 3,920 updates."""
     w = wl.CONFIGS["cfg5"]
-    runs = w.R * w.K if SLOW else 2
+    runs = 2 if QUICK else w.R * w.K
     errs, st = parity_after_every_buffer(w, runs, report=_report("cfg5"))
     assert st.steps == runs * 196
     assert max(e[0] for e in errs) <= TOL_BF16 and max(e[1] for e in errs) <= TOL_BF16
