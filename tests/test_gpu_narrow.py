@@ -86,3 +86,29 @@ def test_other_kernels_keep_their_cases():
         got, st = gpu_run(w, X, y, chain=B.BMGD_CHAIN_PERSISTENT, **kw)
         assert st.threads_per_group == 1024, (kw, p, st.threads_per_group)
         assert rel_l2(got, want) <= TOL
+
+
+def test_more_passes_than_one_launch_holds_and_a_rate_per_update():
+    """Five passes are two launches (four passes, then one): tags, versions and the position in the table of learning
+    rates carry over from launch to launch."""
+    import torch
+    import paper_2312_08728_amd as B
+    from oracle import bmgd as O
+    w = _case(wl.LOGISTIC, 12_000, 200, 6_000, 2048, T=5, R=1, alpha=0.1)
+    X, y = wl.dataset(w)
+    steps = 2 * 5 * 3
+    sched = (0.1 * (0.5 + 0.5 * np.cos(np.pi * np.arange(steps) / steps))).astype(np.float32)
+    ref = O.BMGD(w.model, w.p, w.n, w.alpha, w.T)
+    ref.set_lr_schedule(sched)
+    ctx = B.Context(w.p, w.N0, w.n, w.alpha, w.T, model=w.model, n_workgroups=64, chain=B.BMGD_CHAIN_PERSISTENT)
+    ctx.set_lr_schedule(sched)
+    xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    s = torch.cuda.Stream()
+    for k in range(2):
+        ref.run_buffer(X[k * 6000:(k + 1) * 6000], y[k * 6000:(k + 1) * 6000])
+        ctx.run_device_buffer(xd[k * 6000:(k + 1) * 6000], yd[k * 6000:(k + 1) * 6000], 6000, s)
+    got = ctx.get_theta()
+    st = ctx.stats()
+    ctx.close()
+    assert st.threads_per_group == NARROW_THREADS and st.steps == steps and st.chain_launches == 4
+    assert rel_l2(got, ref.theta) <= TOL
