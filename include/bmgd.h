@@ -116,14 +116,18 @@ enum {
                                     rate and update counts are read from device memory, so a replay needs no new capture.
                                     BMGD_CHAIN_LAUNCH issues the same launches one by one. */
     BMGD_CHAIN_PRODUCT = 5       /* least squares with p <= 128 and plain steps (BMGD_OPT_SGD) only: the moment form of
-                                    BMGD_CHAIN_GRAM with the steps of a launch multiplied together.  A step of eq. (3.1) is the
-                                    affine map [theta; 1] <- A_m [theta; 1], A_m = [[I - alpha Sxx_m, alpha Sxy_m], [0, 1]], and
-                                    no A_m depends on theta, so the estimate after the steps of up to four passes is the
-                                    product A_N ... A_1 applied once (the products of eq. (3.2)); the product is formed pairwise
-                                    in log2 N rounds of small dense products on the matrix cores.  Same result as the chain up
-                                    to the order of the fp32 operations; intermediate estimates are never formed.  Needs scratch
-                                    for N / 2 + N / 4 matrices of (p + 1 rounded up to 16)^2 floats, twice; rejected if that
-                                    exceeds 1 GiB.  Never picked by BMGD_CHAIN_AUTO. */
+                                    BMGD_CHAIN_GRAM with steps multiplied together.  A step of eq. (3.1) is the affine map
+                                    [theta; 1] <- A_m [theta; 1], A_m = [[I - alpha Sxx_m, alpha Sxy_m], [0, 1]], and no A_m
+                                    depends on theta, so products of steps can be formed in parallel on the matrix cores (the
+                                    products of eq. (3.2)).  Neighbouring steps are multiplied in pairs behind the kernel that
+                                    forms the moment matrices, and the sequential chain runs over half as many steps.  With
+                                    cache_moments (fixed partitions) the whole product of a run over a buffer is formed, in
+                                    log2 rounds, and kept per buffer index as long as the learning rate and the number of
+                                    passes stay the same (no table of rates): every later run over that buffer is one
+                                    matrix-vector product.  Same result as the chain up to the order of the fp32 operations;
+                                    intermediate estimates are not formed.  Needs scratch of about 3/4 N matrices of
+                                    (p + 1 rounded up to 16)^2 floats, twice, for the N steps of up to four passes; rejected
+                                    if that exceeds 1 GiB.  Never picked by BMGD_CHAIN_AUTO. */
 };
 
 /* update rule fed with the mini-batch gradient g of eq. (2.1) (Section 4.3 combines the buffering idea with NAG and

@@ -91,6 +91,7 @@ struct bmgd_ctx {
     bool products = false;                         // BMGD_CHAIN_PRODUCT: the steps of a launch multiplied together (gram_products.hip)
     float* prod[2] = {nullptr, nullptr};
     int psel = 0;
+    bool prod_dense[2] = {false, false};           // the set last held dense matrices (the chain's layout needs its padding zero)
     int32_t* gram_perm[2] = {nullptr, nullptr};
     struct CachedMoments {                         // moment matrices of buffer index k under its fixed partition
         bool valid = false;
@@ -465,9 +466,20 @@ hipError_t launch_steps(bmgd_ctx* ctx, const float* set, int64_t rows, int64_t n
         // (launches on one stream run in order, so the scratch of launch k - 2 is free; two sets alternate anyway, so that
         // nothing here depends on that)
         float* scratch = ctx->prod[ctx->psel];
+        const bool pairs = kept == nullptr;
+        if (pairs && ctx->prod_dense[ctx->psel]) {
+            // the pairs go out in the chain's layout, whose padding is read (and multiplied by zeros): clear what a
+            // round of dense matrices left there
+            const size_t bytes = ctx->lay.prod[1] - ctx->lay.prod[0];
+            hipError_t ce = hipMemsetAsync(scratch, 0, bytes, ctx->chain_stream);
+            if (ce != hipSuccess) return ce;
+        }
+        ctx->prod_dense[ctx->psel] = !pairs;
         ctx->psel ^= 1;
+        // Unless the product itself is wanted (to be kept), one round of products is made and the chain runs over the
+        // pairs: every further round costs a kernel's start-up and fills the device, while the chain keeps to one unit.
         hipError_t e = gram_launch_products(set, ctx->theta, scratch, kept, (int)rows, (int)c.p, (int)n, np, perm_stride, (float)c.lr, tab,
-                                            lr_base, lr_len, ctx->chain_stream, ev0, ev1);
+                                            lr_base, lr_len, ctx->chain_stream, ev0, ev1, pairs);
         if (keep) {
             keep->prod_valid = kept != nullptr && e == hipSuccess;
             keep->prod_alpha = (float)c.lr;
@@ -549,13 +561,28 @@ int enqueue_passes(bmgd_ctx* ctx, const void* x, const void* y, int64_t rows, hi
             // set i is free once the chain that read it last has finished
             if (ctx->chain_pending[i]) HIP_TRY(ctx, hipStreamWaitEvent(stream, ctx->chain_done[i], 0));
             HIP_TRY(ctx, launch_perm(ctx->gram_perm[i], rows, nperm, keys, stream, ctx->subset, ctx->subset_limit, ctx->sync + 2));
+            // BMGD_CHAIN_PRODUCT (without cached matrices): the steps are multiplied in pairs right behind the moments
+            // kernel, on the same stream (both fill the device; the chain, which keeps to one unit, overlaps the next
+            // buffer's two), and the chain runs over the pairs.  Set i of the pairs is guarded like set i of the matrices.
+            const bool pairs_here = ctx->products && !c.cache_moments;
             HIP_TRY(ctx, gram_launch_moments(static_cast<const float*>(x), static_cast<const float*>(y), ctx->gram_perm[i],
                                              ctx->gram[i], (int)rows, (int)c.p, (int)n, np, fixed ? 0 : (int)rows, stream,
-                                             pv0, pv1, ctx->products));
+                                             pv0, pairs_here ? nullptr : pv1, ctx->products));
+            if (pairs_here) {
+                HIP_TRY(ctx, gram_launch_pairs(ctx->gram[i], ctx->prod[i], (int)rows, (int)c.p, (int)n, np, fixed ? 0 : (int)rows,
+                                               (float)c.lr, lr_len ? ctx->lr_tab_dev : nullptr,
+                                               (int)std::min<int64_t>(ctx->lr_pos, std::max(lr_len - 1, 0)), lr_len, stream, nullptr, pv1));
+            }
             ctx->prep_done[i] = pv1;
             HIP_TRY(ctx, hipStreamWaitEvent(ctx->chain_stream, ctx->prep_done[i], 0));
             // the timing events are completed by the chain's dispatch; the stop event also frees set i
-            HIP_TRY(ctx, launch_steps(ctx, ctx->gram[i], rows, n, np, fixed ? 0 : (int)rows, ev0, ev1));
+            if (pairs_here) {
+                const int half = (int)(((int64_t)np * M + 1) / 2);
+                HIP_TRY(ctx, gram_launch_chain_steps(ctx->prod[i], ctx->theta, (int)c.p, half, half, 1.0f, nullptr, 0, 0, opt_args(ctx, 0),
+                                                     ctx->chain_stream, ev0, ev1));
+            } else {
+                HIP_TRY(ctx, launch_steps(ctx, ctx->gram[i], rows, n, np, fixed ? 0 : (int)rows, ev0, ev1));
+            }
             ctx->lr_pos += (int64_t)np * M;
             ctx->opt_k += (int64_t)np * M;
             ctx->chain_done[i] = ev1;                // stays valid until the records are settled, after a drain

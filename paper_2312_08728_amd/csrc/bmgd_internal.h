@@ -182,16 +182,26 @@ size_t gram_dense_bytes_per_batch(int64_t p);
 hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, int n, int npass, int perm_stride, float alpha,
                              const float* lr_tab, int lr_base, int lr_len, const OptArgs& opt, hipStream_t stream,
                              hipEvent_t start, hipEvent_t stop);
+// The same chain over nsteps sets of matrices given directly (step s uses set s % period)
+hipError_t gram_launch_chain_steps(const float* gram, float* theta, int p, int nsteps, int period, float alpha, const float* lr_tab,
+                                   int lr_base, int lr_len, const OptArgs& opt, hipStream_t stream, hipEvent_t start,
+                                   hipEvent_t stop);
 // BMGD_CHAIN_PRODUCT (gram_products.hip): the npass * M steps of a launch as affine maps, multiplied together pairwise
 // in log2 rounds and applied to theta once.  `gram`: the dense matrices of gram_launch_moments(..., dense = true).
 // `scratch`: gram_products_scratch_floats(p, npass * M) floats.  Plain steps only.
 size_t gram_products_scratch_floats(int64_t p, int64_t max_steps);
 hipError_t gram_launch_products(const float* gram, float* theta, float* scratch, float* product_out, int rows, int p, int n, int npass,
                                 int perm_stride, float alpha, const float* lr_tab, int lr_base, int lr_len, hipStream_t stream,
-                                hipEvent_t start, hipEvent_t stop);
+                                hipEvent_t start, hipEvent_t stop, bool pairs_then_chain = false);
 // product_out (optional): where the product of the launch's steps is left, gram_dense_order(p)^2 floats; gram_launch_apply
-// applies such a product to theta again (fixed partitions, constant rate: the product of a buffer is the same every time)
+// applies such a product to theta again (fixed partitions, constant rate: the product of a buffer is the same every time).
+// pairs_then_chain: one round only - neighbouring steps multiplied in pairs, written as [I - A | d] in the chain's layout -
+// and the chain of eq. (3.1) then runs over half as many steps (with rate 1: theta - (I - A) theta + d = A theta + d)
 hipError_t gram_launch_apply(const float* product, float* theta, int p, hipStream_t stream, hipEvent_t start, hipEvent_t stop);
+// One round only: the launch's steps multiplied in neighbouring pairs, each product P written as [I - P | last column of P]
+// in the layout of the chain's moment matrices ((npass * M + 1) / 2 sets), so that gram_launch_chain_steps with rate 1 applies them
+hipError_t gram_launch_pairs(const float* gram, float* pairs_out, int rows, int p, int n, int npass, int perm_stride, float alpha,
+                             const float* lr_tab, int lr_base, int lr_len, hipStream_t stream, hipEvent_t start, hipEvent_t stop);
 
 // ---------------------------------------------------------------------------------------------------
 // Softmax regression (bf16 predictors, fp32 master weights) on the matrix cores.

@@ -400,10 +400,17 @@ hipError_t gram_launch_chain(const float* gram, float* theta, int rows, int p, i
                              const float* lr_tab, int lr_base, int lr_len, const OptArgs& opt, hipStream_t stream,
                              hipEvent_t start, hipEvent_t stop)
 {
-    if (p < 1 || p > kGramMaxP) return hipErrorInvalidValue;
-    const GramLayout L = make_layout(p);
     const int M = (rows + n - 1) / n;
     const int nsteps = M * npass, period = perm_stride == 0 ? M : nsteps;
+    return gram_launch_chain_steps(gram, theta, p, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);
+}
+
+hipError_t gram_launch_chain_steps(const float* gram, float* theta, int p, int nsteps, int period, float alpha, const float* lr_tab,
+                                   int lr_base, int lr_len, const OptArgs& opt, hipStream_t stream, hipEvent_t start,
+                                   hipEvent_t stop)
+{
+    if (p < 1 || p > kGramMaxP || nsteps < 1 || period < 1) return hipErrorInvalidValue;
+    const GramLayout L = make_layout(p);
     if (L.tpr == 16) {
         switch (L.kq) {
         case 0: return launch_chain_ks<16, 0>(L, gram, theta, nsteps, period, alpha, lr_tab, lr_base, lr_len, opt, stream, start, stop);

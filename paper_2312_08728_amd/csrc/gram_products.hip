@@ -9,6 +9,7 @@
 // intermediate estimates are not formed.
 #include "bmgd_internal.h"
 #include "glm_device.h"
+#include "gram_layout.h"
 
 #include <hip/hip_ext.h>
 
@@ -45,9 +46,11 @@ constexpr int kMaxLeftVec = (16 * kMaxOrder / 4 + kPairThreads - 1) / kPairThrea
 // (v_mfma_f32_16x16x4_f32): a = A[lane % 16][lane / 16], b = B[lane / 16][lane % 16], c[v] = C[4 (lane / 16) + v][lane % 16].
 // FIRST: the factors are the steps themselves, A_s = [[I - alpha_s Sxx_s, alpha_s Sxy_s], [0, 1]] padded with zeros:
 // entry (r, c) is (r == c and r <= p) - alpha_s D_s(r, c) with D_s the dense matrix the moments kernel wrote.
-template <bool FIRST>
+// CHAIN_OUT: the product P goes out as [I - P | last column of P] in the layout the chain kernel reads (GramLayout), so
+// that the chain's step theta - 1 * ((I - P) theta - d) applies it.
+template <bool FIRST, bool CHAIN_OUT = false>
 __global__ void __launch_bounds__(kPairThreads) affine_pair_kernel(FirstLevel f, const float* __restrict__ in, float* __restrict__ out,
-                                                                   int count_in, int Q, int rs, unsigned qv_inv)
+                                                                   int count_in, int Q, int rs, unsigned qv_inv, GramLayout L)
 {
     extern __shared__ __align__(16) float lds[];
     const int ls = Q + 4;                            // row stride of the left factor's rows: float4 stores stay aligned, and a
@@ -133,14 +136,21 @@ __global__ void __launch_bounds__(kPairThreads) affine_pair_kernel(FirstLevel f,
                 if (wave + 4 * t < NT)               // (the same for the whole wavefront)
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q], b[q][t], acc[t], 0, 0, 0);
     }
-    float* o = out + (size_t)j * Q * Q;
+    float* o = out + (size_t)j * (CHAIN_OUT ? (size_t)L.step_floats : (size_t)Q * Q);
 #pragma unroll
     for (int t = 0; t < kMaxTilesPerWave; ++t) {
         const int tc = wave + 4 * t;
         if (tc < NT) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                o[(size_t)(16 * tr + 4 * (lane >> 4) + v) * Q + 16 * tc + (lane & 15)] = acc[t][v];
+            for (int v = 0; v < 4; ++v) {
+                const int r = 16 * tr + 4 * (lane >> 4) + v, c = 16 * tc + (lane & 15);
+                if constexpr (CHAIN_OUT) {
+                    if (r < L.p && c < L.p) o[gram_pos(L, r, c)] = (r == c ? 1.f : 0.f) - acc[t][v];
+                    else if (r < L.p && c == L.p) o[L.b_off + r] = acc[t][v];
+                } else {
+                    o[(size_t)r * Q + c] = acc[t][v];
+                }
+            }
         }
     }
 }
@@ -181,7 +191,8 @@ size_t gram_products_scratch_floats(int64_t p, int64_t max_steps)
 {
     const size_t Q = (size_t)padded_order((int)p);
     const size_t half = (size_t)(max_steps + 1) / 2, quarter = (half + 1) / 2;
-    return (half + quarter) * Q * Q;
+    const size_t per = std::max(Q * Q, (size_t)make_layout((int)p).step_floats);       // dense, or in the chain's layout
+    return (half + quarter) * per;
 }
 
 hipError_t gram_launch_apply(const float* product, float* theta, int p, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
@@ -191,17 +202,29 @@ hipError_t gram_launch_apply(const float* product, float* theta, int p, hipStrea
     return hipGetLastError();
 }
 
-hipError_t gram_launch_products(const float* gram, float* theta, float* scratch, float* product_out, int rows, int p, int n, int npass,
-                                int perm_stride, float alpha, const float* lr_tab, int lr_base, int lr_len, hipStream_t stream,
-                                hipEvent_t start, hipEvent_t stop)
+namespace {
+
+// what every launch of the pair kernel needs
+struct PairSetup {
+    int N, Q, NT, rs;
+    size_t lds;
+    unsigned qv_inv;
+    FirstLevel f;
+};
+
+hipError_t pair_setup(const float* gram, int rows, int p, int n, int npass, int perm_stride, float alpha, const float* lr_tab,
+                      int lr_base, int lr_len, PairSetup* out)
 {
     if (p < 1 || p > kGramMaxP) return hipErrorInvalidValue;
     const int M = (rows + n - 1) / n;
-    const int N = M * npass;
-    const int Q = padded_order(p), NT = Q / 16;
-    if (NT > 4 * kMaxTilesPerWave) return hipErrorInvalidValue;
-    const int rs = Q % 32 == 0 ? Q + 16 : Q;
-    const size_t lds = sizeof(float) * (size_t)(16 * (Q + 4) + Q * rs);
+    PairSetup s{};
+    s.N = M * npass;
+    s.Q = padded_order(p);
+    s.NT = s.Q / 16;
+    if (s.NT > 4 * kMaxTilesPerWave) return hipErrorInvalidValue;
+    s.rs = s.Q % 32 == 0 ? s.Q + 16 : s.Q;
+    s.lds = sizeof(float) * (size_t)(16 * (s.Q + 4) + s.Q * s.rs);
+    s.qv_inv = (1u << 20) / (unsigned)(s.Q / 4) + 1u;
     static bool attr_set = false;                    // (per process: the attribute belongs to the function)
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(affine_pair_kernel<true>),
@@ -209,25 +232,67 @@ hipError_t gram_launch_products(const float* gram, float* theta, float* scratch,
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(affine_pair_kernel<false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(affine_pair_kernel<true, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    FirstLevel f{};
-    f.dense = gram;
-    f.p = p;
-    f.period = perm_stride == 0 ? M : N;
-    f.alpha = alpha;
-    f.lr_tab = lr_tab;
-    f.lr_base = lr_base;
-    f.lr_len = lr_len;
-    const unsigned qv_inv = (1u << 20) / (unsigned)(Q / 4) + 1u;
+    s.f.dense = gram;
+    s.f.p = p;
+    s.f.period = perm_stride == 0 ? M : s.N;
+    s.f.alpha = alpha;
+    s.f.lr_tab = lr_tab;
+    s.f.lr_base = lr_base;
+    s.f.lr_len = lr_len;
+    *out = s;
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t gram_launch_pairs(const float* gram, float* pairs_out, int rows, int p, int n, int npass, int perm_stride, float alpha,
+                             const float* lr_tab, int lr_base, int lr_len, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
+{
+    PairSetup s;
+    hipError_t e = pair_setup(gram, rows, p, n, npass, perm_stride, alpha, lr_tab, lr_base, lr_len, &s);
+    if (e != hipSuccess) return e;
+    hipExtLaunchKernelGGL((affine_pair_kernel<true, true>), dim3(s.NT, (s.N + 1) / 2), dim3(kPairThreads), (uint32_t)s.lds, stream, start,
+                          stop, 0u, s.f, static_cast<const float*>(nullptr), pairs_out, s.N, s.Q, s.rs, s.qv_inv, make_layout(p));
+    return hipGetLastError();
+}
+
+hipError_t gram_launch_products(const float* gram, float* theta, float* scratch, float* product_out, int rows, int p, int n, int npass,
+                                int perm_stride, float alpha, const float* lr_tab, int lr_base, int lr_len, hipStream_t stream,
+                                hipEvent_t start, hipEvent_t stop, bool pairs_then_chain)
+{
+    PairSetup ps;
+    {
+        hipError_t e0 = pair_setup(gram, rows, p, n, npass, perm_stride, alpha, lr_tab, lr_base, lr_len, &ps);
+        if (e0 != hipSuccess) return e0;
+    }
+    const int N = ps.N, Q = ps.Q, NT = ps.NT, rs = ps.rs;
+    const size_t lds = ps.lds;
+    const unsigned qv_inv = ps.qv_inv;
+    const FirstLevel f = ps.f;
+    const GramLayout L = make_layout(p);
+    if (pairs_then_chain) {
+        // one round of products into the chain's layout, then the chain over half as many steps, each applied with rate 1
+        hipError_t e = gram_launch_pairs(gram, scratch, rows, p, n, npass, perm_stride, alpha, lr_tab, lr_base, lr_len, stream, start,
+                                         nullptr);
+        if (e != hipSuccess) return e;
+        OptArgs none{};
+        none.kind = kOptSgd;
+        const int half = (N + 1) / 2;
+        return gram_launch_chain_steps(scratch, theta, p, half, half, 1.0f, nullptr, 0, 0, none, stream, nullptr, stop);
+    }
     float* buf[2] = {scratch, scratch + (size_t)((N + 1) / 2) * Q * Q};
     // the round that leaves one matrix writes it where the caller wants the product of the launch
     float* fin = product_out ? product_out : buf[0];
     int count = N, which = 0;
     // round 0 reads the moment matrices; the start event rides on its dispatch, the stop event on the last one's
     hipExtLaunchKernelGGL(affine_pair_kernel<true>, dim3(NT, (count + 1) / 2), dim3(kPairThreads), (uint32_t)lds, stream, start, nullptr,
-                          0u, f, static_cast<const float*>(nullptr), count <= 2 ? fin : buf[0], count, Q, rs, qv_inv);
+                          0u, f, static_cast<const float*>(nullptr), count <= 2 ? fin : buf[0], count, Q, rs, qv_inv, L);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const float* cur = count <= 2 ? fin : buf[0];
@@ -236,7 +301,7 @@ hipError_t gram_launch_products(const float* gram, float* theta, float* scratch,
         float* dst = count <= 2 ? fin : buf[which ^ 1];
         if (dst == cur) dst = buf[which ^ 1];        // (no product_out: the last round must not write what it reads)
         hipLaunchKernelGGL(affine_pair_kernel<false>, dim3(NT, (count + 1) / 2), dim3(kPairThreads), lds, stream, f, cur, dst, count, Q,
-                           rs, qv_inv);
+                           rs, qv_inv, L);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         cur = dst;
         count = (count + 1) / 2;

@@ -76,7 +76,9 @@ def test_products_refuse_what_they_cannot_do():
 def test_products_over_cached_moment_matrices():
     """Fixed partitions with the moment matrices of every buffer kept on the device: iterations after the first read no
     row, and while the learning rate and the number of passes stay the same the product of a buffer's steps is kept too
-    and only applied.  Same estimate, bit for bit, as without the cache; a new learning rate makes new products."""
+    and only applied.  Same estimate as without the cache up to fp32 rounding (without the cache the steps are multiplied
+    in pairs and the chain runs over the pairs; the kept product is the whole product); a new learning rate makes new
+    products."""
     import torch
     import paper_2312_08728_amd as B
     w = _case(8000, 40, 4000, 250, 3, 3, 0.02)
@@ -99,7 +101,7 @@ def test_products_over_cached_moment_matrices():
     for _ in range(3):
         sweep(plain, False)
     got = ctx.get_theta()
-    assert np.array_equal(got, plain.get_theta())
+    assert rel_l2(got, plain.get_theta()) <= 1e-5
     assert rel_l2(got, want) <= TOL
     assert ctx.stats().steps == 3 * 2 * 3 * 16
     for c in (ctx, plain):
@@ -108,6 +110,17 @@ def test_products_over_cached_moment_matrices():
     sweep(ctx, True)
     sweep(plain, False)
     sweep(plain, False)
-    assert np.array_equal(ctx.get_theta(), plain.get_theta())
+    assert rel_l2(ctx.get_theta(), plain.get_theta()) <= 1e-5
+    # the kept products are applied the same way every time: a second context gives the same bits
+    again = B.Context(w.p, w.N0, w.n, w.alpha, w.T, chain=B.BMGD_CHAIN_PRODUCT, reshuffle=B.BMGD_RESHUFFLE_FIXED, n_buffers=2,
+                      cache_moments=True)
+    sweep(again, False)
+    sweep(again, True)
+    sweep(again, True)
+    again.set_lr(0.01)
+    sweep(again, True)
+    sweep(again, True)
+    assert np.array_equal(again.get_theta(), ctx.get_theta())
+    again.close()
     ctx.close()
     plain.close()
