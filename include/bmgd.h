@@ -154,7 +154,9 @@ typedef struct bmgd_config {
     int32_t  n_buffers;    /* K; used only by BMGD_RESHUFFLE_FIXED (partition index = buffer counter mod K);
                               0 = use the buffer counter itself */
     int32_t  chain;        /* BMGD_CHAIN_* */
-    int32_t  n_workgroups; /* workgroups taking part in each step; 0 = chosen from the shape */
+    int32_t  n_workgroups; /* workgroups taking part in each step; 0 = chosen from the shape.  At most one per compute unit;
+                              two of the persistent kernels take multiples of 8 (a request is rounded down; bmgd_get_stats
+                              reports what is used) */
     int64_t  barrier_timeout_us; /* upper bound on any single device-side wait; 0 = default (2 s).
                               A wait that exceeds it makes the kernel exit and the next blocking call
                               return BMGD_EHIP. */
