@@ -892,6 +892,7 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->prod[0] = reinterpret_cast<float*>(base + ctx->lay.prod[0]);
     ctx->prod[1] = reinterpret_cast<float*>(base + ctx->lay.prod[1]);
     ctx->products = cfg->chain == BMGD_CHAIN_PRODUCT;
+    if (ctx->products) CREATE_TRY(gram_products_prepare());
     ctx->gram_cache = base + ctx->lay.gram_cache;
     ctx->prod_cache = base + ctx->lay.prod_cache;
     if (cfg->cache_moments) ctx->mcache.resize((size_t)cfg->n_buffers);

@@ -190,6 +190,8 @@ hipError_t gram_launch_chain_steps(const float* gram, float* theta, int p, int n
 // in log2 rounds and applied to theta once.  `gram`: the dense matrices of gram_launch_moments(..., dense = true).
 // `scratch`: gram_products_scratch_floats(p, npass * M) floats.  Plain steps only.
 size_t gram_products_scratch_floats(int64_t p, int64_t max_steps);
+// once per device with that device current, before the first launch below (raises the kernels' shared-memory limit)
+hipError_t gram_products_prepare();
 hipError_t gram_launch_products(const float* gram, float* theta, float* scratch, float* product_out, int rows, int p, int n, int npass,
                                 int perm_stride, float alpha, const float* lr_tab, int lr_base, int lr_len, hipStream_t stream,
                                 hipEvent_t start, hipEvent_t stop, bool pairs_then_chain = false);

@@ -225,19 +225,6 @@ hipError_t pair_setup(const float* gram, int rows, int p, int n, int npass, int 
     s.rs = s.Q % 32 == 0 ? s.Q + 16 : s.Q;
     s.lds = sizeof(float) * (size_t)(16 * (s.Q + 4) + s.Q * s.rs);
     s.qv_inv = (1u << 20) / (unsigned)(s.Q / 4) + 1u;
-    static bool attr_set = false;                    // (per process: the attribute belongs to the function)
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(affine_pair_kernel<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(affine_pair_kernel<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(affine_pair_kernel<true, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     s.f.dense = gram;
     s.f.p = p;
     s.f.period = perm_stride == 0 ? M : s.N;
@@ -250,6 +237,18 @@ hipError_t pair_setup(const float* gram, int rows, int p, int n, int npass, int 
 }
 
 }  // namespace
+
+hipError_t gram_products_prepare()
+{
+    // the pair kernel stages up to 92 KB in shared memory (order 144): above the default limit of a launch
+    const int bytes = 160 * 1024 - 64;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(affine_pair_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(affine_pair_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(affine_pair_kernel<true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    return e;
+}
 
 hipError_t gram_launch_pairs(const float* gram, float* pairs_out, int rows, int p, int n, int npass, int perm_stride, float alpha,
                              const float* lr_tab, int lr_base, int lr_len, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
