@@ -35,12 +35,13 @@ struct FirstLevel {                                  // where the steps' moment 
 
 constexpr int kMaxOrder = (kGramMaxP + 1 + 15) / 16 * 16;                       // 144
 constexpr int kMaxRightVec = (kMaxOrder * kMaxOrder / 4 + kPairThreads - 1) / kPairThreads;   // float4 of the right factor per thread
-constexpr int kMaxLeftVec = (16 * kMaxOrder / 4 + kPairThreads - 1) / kPairThreads;           // of the left factor's 16 rows
+constexpr int kTileRows = 2;                          // 16-row tile rows of a product per workgroup (the right factor is staged once for both)
+constexpr int kMaxLeftVec = (16 * kTileRows * kMaxOrder / 4 + kPairThreads - 1) / kPairThreads;   // of the left factor's rows
 
 // out[j] = in[2 j + 1] * in[2 j] (the later step on the left); a missing in[2 j + 1] counts as the identity.  Dense
-// Q x Q matrices, row-major, Q a multiple of 16.  Workgroup (x, y) computes tile row x of out[y]: it stages the 16 rows of
-// the left factor and the whole right factor in shared memory and each wavefront takes every fourth 16 x 16 tile of the
-// row.  Everything a thread stages is requested first and stored afterwards (unconditional loads from clamped
+// Q x Q matrices, row-major, Q a multiple of 16.  Workgroup (x, y) computes the tile rows 2 x and 2 x + 1 of out[y]: it stages
+// their 32 rows of the left factor and the whole right factor in shared memory and each wavefront takes every fourth 16 x 16
+// tile of both rows.  Everything a thread stages is requested first and stored afterwards (unconditional loads from clamped
 // addresses), so the staging costs one trip to memory, not one per element; row and column of a float4 come from a
 // multiplication (qv_inv = 2^20 / (Q / 4) + 1: exact for the 5184 float4 of the largest matrix).  MFMA operand layout
 // (v_mfma_f32_16x16x4_f32): a = A[lane % 16][lane / 16], b = B[lane / 16][lane % 16], c[v] = C[4 (lane / 16) + v][lane % 16].
@@ -55,10 +56,11 @@ __global__ void __launch_bounds__(kPairThreads) affine_pair_kernel(FirstLevel f,
     extern __shared__ __align__(16) float lds[];
     const int ls = Q + 4;                            // row stride of the left factor's rows: float4 stores stay aligned, and a
     float* Ls = lds;                                 // column read (16 rows, one k) meets each bank at most twice
-    float* Rs = lds + 16 * ls;                       // right factor, row stride rs = 16 (mod 32): four rows of 16 columns apart
+    float* Rs = lds + 16 * kTileRows * ls;           // right factor, row stride rs = 16 (mod 32): four rows of 16 columns apart
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int NT = Q / 16, QV = Q / 4;
-    const int tr = blockIdx.x, j = blockIdx.y;
+    const int tr = kTileRows * blockIdx.x, j = blockIdx.y;   // first tile row of this workgroup
+    const int nrows = 16 * min(kTileRows, NT - tr);  // rows of the left factor it needs
     const int right = 2 * j, left = 2 * j + 1;
     const bool has_left = left < count_in;
     const int lc = has_left ? left : right;          // (clamped: not used when the left factor is the identity)
@@ -75,7 +77,7 @@ __global__ void __launch_bounds__(kPairThreads) affine_pair_kernel(FirstLevel f,
         Rm = in + (size_t)right * Q * Q;
         Lm = in + (size_t)lc * Q * Q + (size_t)16 * tr * Q;        // its 16 rows are contiguous
     }
-    const int nR = Q * QV, nL = 16 * QV;
+    const int nR = Q * QV, nL = nrows * QV;
     float4 rv[kMaxRightVec], lv[kMaxLeftVec];
 #pragma unroll
     for (int i = 0; i < kMaxRightVec; ++i)
@@ -115,17 +117,21 @@ __global__ void __launch_bounds__(kPairThreads) affine_pair_kernel(FirstLevel f,
     }
     __syncthreads();
 
-    floatx4 acc[kMaxTilesPerWave];
+    floatx4 acc[kTileRows][kMaxTilesPerWave];
 #pragma unroll
-    for (int t = 0; t < kMaxTilesPerWave; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int h = 0; h < kTileRows; ++h)
+#pragma unroll
+        for (int t = 0; t < kMaxTilesPerWave; ++t) acc[h][t] = floatx4{0.f, 0.f, 0.f, 0.f};
     const float* ap = Ls + (lane & 15) * ls + (lane >> 4);
     const float* bp = Rs + (lane >> 4) * rs + (lane & 15);
+    const bool two = nrows > 16;                     // (the same for the whole workgroup)
     // (Q is a multiple of 16: four K steps per trip, their operand reads issued together)
     for (int k0 = 0; k0 < Q; k0 += 16) {
-        float a[4], b[4][kMaxTilesPerWave];
+        float a[4][kTileRows], b[4][kMaxTilesPerWave];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            a[q] = ap[k0 + 4 * q];
+#pragma unroll
+            for (int h = 0; h < kTileRows; ++h) a[q][h] = ap[(two ? 16 * h : 0) * ls + k0 + 4 * q];
 #pragma unroll
             for (int t = 0; t < kMaxTilesPerWave; ++t) b[q][t] = bp[(k0 + 4 * q) * rs + 16 * min(wave + 4 * t, NT - 1)];
         }
@@ -133,22 +139,28 @@ __global__ void __launch_bounds__(kPairThreads) affine_pair_kernel(FirstLevel f,
         for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int t = 0; t < kMaxTilesPerWave; ++t)
-                if (wave + 4 * t < NT)               // (the same for the whole wavefront)
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q], b[q][t], acc[t], 0, 0, 0);
+                if (wave + 4 * t < NT) {             // (the same for the whole wavefront)
+                    acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q][0], b[q][t], acc[0][t], 0, 0, 0);
+                    if (two) acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[q][1], b[q][t], acc[1][t], 0, 0, 0);
+                }
     }
     float* o = out + (size_t)j * (CHAIN_OUT ? (size_t)L.step_floats : (size_t)Q * Q);
 #pragma unroll
-    for (int t = 0; t < kMaxTilesPerWave; ++t) {
-        const int tc = wave + 4 * t;
-        if (tc < NT) {
+    for (int h = 0; h < kTileRows; ++h) {
+        if (16 * h >= nrows) break;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int r = 16 * tr + 4 * (lane >> 4) + v, c = 16 * tc + (lane & 15);
-                if constexpr (CHAIN_OUT) {
-                    if (r < L.p && c < L.p) o[gram_pos(L, r, c)] = (r == c ? 1.f : 0.f) - acc[t][v];
-                    else if (r < L.p && c == L.p) o[L.b_off + r] = acc[t][v];
-                } else {
-                    o[(size_t)r * Q + c] = acc[t][v];
+        for (int t = 0; t < kMaxTilesPerWave; ++t) {
+            const int tc = wave + 4 * t;
+            if (tc < NT) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int r = 16 * (tr + h) + 4 * (lane >> 4) + v, c = 16 * tc + (lane & 15);
+                    if constexpr (CHAIN_OUT) {
+                        if (r < L.p && c < L.p) o[gram_pos(L, r, c)] = (r == c ? 1.f : 0.f) - acc[h][t][v];
+                        else if (r < L.p && c == L.p) o[L.b_off + r] = acc[h][t][v];
+                    } else {
+                        o[(size_t)r * Q + c] = acc[h][t][v];
+                    }
                 }
             }
         }
@@ -223,7 +235,7 @@ hipError_t pair_setup(const float* gram, int rows, int p, int n, int npass, int 
     s.NT = s.Q / 16;
     if (s.NT > 4 * kMaxTilesPerWave) return hipErrorInvalidValue;
     s.rs = s.Q % 32 == 0 ? s.Q + 16 : s.Q;
-    s.lds = sizeof(float) * (size_t)(16 * (s.Q + 4) + s.Q * s.rs);
+    s.lds = sizeof(float) * (size_t)(16 * kTileRows * (s.Q + 4) + s.Q * s.rs);
     s.qv_inv = (1u << 20) / (unsigned)(s.Q / 4) + 1u;
     s.f.dense = gram;
     s.f.p = p;
@@ -256,7 +268,7 @@ hipError_t gram_launch_pairs(const float* gram, float* pairs_out, int rows, int 
     PairSetup s;
     hipError_t e = pair_setup(gram, rows, p, n, npass, perm_stride, alpha, lr_tab, lr_base, lr_len, &s);
     if (e != hipSuccess) return e;
-    hipExtLaunchKernelGGL((affine_pair_kernel<true, true>), dim3(s.NT, (s.N + 1) / 2), dim3(kPairThreads), (uint32_t)s.lds, stream, start,
+    hipExtLaunchKernelGGL((affine_pair_kernel<true, true>), dim3((s.NT + kTileRows - 1) / kTileRows, (s.N + 1) / 2), dim3(kPairThreads), (uint32_t)s.lds, stream, start,
                           stop, 0u, s.f, static_cast<const float*>(nullptr), pairs_out, s.N, s.Q, s.rs, s.qv_inv, make_layout(p));
     return hipGetLastError();
 }
@@ -290,7 +302,7 @@ hipError_t gram_launch_products(const float* gram, float* theta, float* scratch,
     float* fin = product_out ? product_out : buf[0];
     int count = N, which = 0;
     // round 0 reads the moment matrices; the start event rides on its dispatch, the stop event on the last one's
-    hipExtLaunchKernelGGL(affine_pair_kernel<true>, dim3(NT, (count + 1) / 2), dim3(kPairThreads), (uint32_t)lds, stream, start, nullptr,
+    hipExtLaunchKernelGGL(affine_pair_kernel<true>, dim3((NT + kTileRows - 1) / kTileRows, (count + 1) / 2), dim3(kPairThreads), (uint32_t)lds, stream, start, nullptr,
                           0u, f, static_cast<const float*>(nullptr), count <= 2 ? fin : buf[0], count, Q, rs, qv_inv, L);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -299,7 +311,7 @@ hipError_t gram_launch_products(const float* gram, float* theta, float* scratch,
     while (count > 1) {
         float* dst = count <= 2 ? fin : buf[which ^ 1];
         if (dst == cur) dst = buf[which ^ 1];        // (no product_out: the last round must not write what it reads)
-        hipLaunchKernelGGL(affine_pair_kernel<false>, dim3(NT, (count + 1) / 2), dim3(kPairThreads), lds, stream, f, cur, dst, count, Q,
+        hipLaunchKernelGGL(affine_pair_kernel<false>, dim3((NT + kTileRows - 1) / kTileRows, (count + 1) / 2), dim3(kPairThreads), lds, stream, f, cur, dst, count, Q,
                            rs, qv_inv, L);
         if ((e = hipGetLastError()) != hipSuccess) return e;
         cur = dst;
