@@ -109,7 +109,8 @@ enum {
                                     mini-batch of a pass are formed first, in parallel over the buffer (each row
                                     read once), and the sequential chain then runs inside one workgroup at p^2
                                     multiply-adds per step.  Same result as the row form up to the order of
-                                    summation.  BMGD_CHAIN_AUTO picks it when it applies and batch_n >= 2 p. */
+                                    summation.  BMGD_CHAIN_AUTO picks the moment form when it applies and batch_n >= 2 p: this
+                                    mode, or BMGD_CHAIN_PRODUCT (see there). */
     BMGD_CHAIN_GRAPH = 4,        /* softmax only (its BMGD_CHAIN_AUTO): the launches of one pass over one buffer - the transpose of
                                     its mini-batches, then logits, residual and gradient + update per mini-batch - are captured
                                     once into a HIP graph per (buffer address, rows, partition slot) and replayed; learning
@@ -127,7 +128,9 @@ enum {
                                     matrix-vector product.  Same result as the chain up to the order of the fp32 operations;
                                     intermediate estimates are not formed.  Needs scratch of about 3/4 N matrices of
                                     (p + 1 rounded up to 16)^2 floats, twice, for the N steps of up to four passes; rejected
-                                    if that exceeds 1 GiB.  Never picked by BMGD_CHAIN_AUTO. */
+                                    if that exceeds 1 GiB.  BMGD_CHAIN_AUTO picks it, in place of BMGD_CHAIN_GRAM, for plain
+                                    steps without cache_moments when a launch has at least 64 steps (bmgd_get_stats reports
+                                    the mode in use). */
 };
 
 /* update rule fed with the mini-batch gradient g of eq. (2.1) (Section 4.3 combines the buffering idea with NAG and

@@ -217,6 +217,19 @@ bool valid_config(const bmgd_config& c, std::string* why)
 
 int resolve_chain(const bmgd_config& c);
 
+// BMGD_CHAIN_PRODUCT, asked for or picked: BMGD_CHAIN_AUTO takes it for plain steps of least squares in the moment form
+// when a launch has enough steps for the halved chain to matter (measured at 300 steps per launch: 0.151 against 0.175 ms
+// per buffer) and nothing is cached (with cached matrices the caller chooses between the two forms).
+bool wants_products(const bmgd_config& c)
+{
+    if (c.chain == BMGD_CHAIN_PRODUCT) return true;
+    if (c.chain != BMGD_CHAIN_AUTO || !gram_eligible(c.model, c.p, c.batch_n) || c.optimizer != BMGD_OPT_SGD || c.cache_moments)
+        return false;
+    const int64_t M = (c.buffer_n + c.batch_n - 1) / c.batch_n;
+    const int64_t steps = (int64_t)std::min<int64_t>(kMaxPassesPerLaunch, c.passes) * M;
+    return steps >= 64 && gram_products_scratch_floats(c.p, (int64_t)kMaxPassesPerLaunch * M) <= (size_t(1) << 26);
+}
+
 Layout make_layout(const bmgd_config& c)
 {
     Layout l{};
@@ -251,14 +264,14 @@ Layout make_layout(const bmgd_config& c)
     l.gram[0] = l.gram[1] = l.gram_perm = off;
     if (resolve_chain(c) == BMGD_CHAIN_GRAM) {
         const size_t set = align_up((size_t)kMaxPassesPerLaunch * (size_t)((c.buffer_n + c.batch_n - 1) / c.batch_n) *
-                                    (c.chain == BMGD_CHAIN_PRODUCT ? gram_dense_bytes_per_batch(c.p) : gram_bytes_per_batch(c.p)));
+                                    (wants_products(c) ? gram_dense_bytes_per_batch(c.p) : gram_bytes_per_batch(c.p)));
         l.gram[0] = off; off += set;
         l.gram[1] = off; off += set;
         l.gram_perm = off; off += align_up((size_t)kMaxPassesPerLaunch * c.buffer_n * 4);   // second set of partitions
     }
     // BMGD_CHAIN_PRODUCT: two sets of scratch for the products of a launch's steps
     l.prod[0] = l.prod[1] = off;
-    if (c.chain == BMGD_CHAIN_PRODUCT) {
+    if (wants_products(c)) {
         const size_t set = align_up(4 * gram_products_scratch_floats(c.p, (int64_t)kMaxPassesPerLaunch * ((c.buffer_n + c.batch_n - 1) / c.batch_n)));
         l.prod[0] = off; off += set;
         l.prod[1] = off; off += set;
@@ -268,13 +281,13 @@ Layout make_layout(const bmgd_config& c)
     l.gram_cache_set = 0;
     if (c.cache_moments) {
         l.gram_cache_set = align_up((size_t)((c.buffer_n + c.batch_n - 1) / c.batch_n) *
-                                    (c.chain == BMGD_CHAIN_PRODUCT ? gram_dense_bytes_per_batch(c.p) : gram_bytes_per_batch(c.p)));
+                                    (wants_products(c) ? gram_dense_bytes_per_batch(c.p) : gram_bytes_per_batch(c.p)));
         off += l.gram_cache_set * (size_t)c.n_buffers;
     }
     // BMGD_CHAIN_PRODUCT with cached moment matrices: per buffer index also the product of a run's steps
     l.prod_cache = off;
     l.prod_cache_set = 0;
-    if (c.cache_moments && c.chain == BMGD_CHAIN_PRODUCT) {
+    if (c.cache_moments && wants_products(c)) {
         l.prod_cache_set = align_up(gram_dense_bytes_per_batch(c.p));
         off += l.prod_cache_set * (size_t)c.n_buffers;
     }
@@ -300,7 +313,7 @@ Layout make_layout(const bmgd_config& c)
 int resolve_chain(const bmgd_config& c)
 {
     if (c.model == BMGD_SOFTMAX) return c.chain == BMGD_CHAIN_LAUNCH ? BMGD_CHAIN_LAUNCH : BMGD_CHAIN_GRAPH;
-    if (c.chain == BMGD_CHAIN_PRODUCT) return BMGD_CHAIN_GRAM;      // the moment form with another way through the steps (ctx->products)
+    if (wants_products(c)) return BMGD_CHAIN_GRAM;                  // the moment form with another way through the steps (ctx->products)
     if (c.chain != BMGD_CHAIN_AUTO) return c.chain;
     return gram_eligible(c.model, c.p, c.batch_n) ? BMGD_CHAIN_GRAM : BMGD_CHAIN_PERSISTENT;
 }
@@ -891,7 +904,7 @@ BMGD_API int bmgd_create_ex(const bmgd_config* cfg, bmgd_ctx** out)
     ctx->gram[1] = reinterpret_cast<float*>(base + ctx->lay.gram[1]);
     ctx->prod[0] = reinterpret_cast<float*>(base + ctx->lay.prod[0]);
     ctx->prod[1] = reinterpret_cast<float*>(base + ctx->lay.prod[1]);
-    ctx->products = cfg->chain == BMGD_CHAIN_PRODUCT;
+    ctx->products = wants_products(*cfg);
     if (ctx->products) CREATE_TRY(gram_products_prepare());
     ctx->gram_cache = base + ctx->lay.gram_cache;
     ctx->prod_cache = base + ctx->lay.prod_cache;

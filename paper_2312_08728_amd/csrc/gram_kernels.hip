@@ -40,7 +40,9 @@ constexpr int kGramWaves = 4;
 // their TPW tiles of [X y]' [X y]; the four partial sums meet in LDS, are divided by n_b and written in the
 // chain's layout (both triangles).  MFMA operand layout (v_mfma_f32_16x16x4_f32): a = A[lane % 16][lane / 16],
 // b = B[lane / 16][lane % 16], c[v] = C[4 (lane / 16) + v][lane % 16]; here A = (staged rows)' and B = staged rows.
-template <int TPW, bool WIDE>
+// VEC: p is a multiple of 4 and rows are moved as float4 (a quarter of the load, address and store instructions; the
+// kernel is bound by instruction issue, not by any one unit).
+template <int TPW, bool WIDE, bool VEC>
 __global__ void __launch_bounds__(64 * kGramWaves) gram_mfma_kernel(const float* __restrict__ X, const float* __restrict__ y,
                                                                      const int* __restrict__ perm, float* __restrict__ out,
                                                                      int rows, int n, int perm_stride, int M, int n_items,
@@ -76,35 +78,73 @@ __global__ void __launch_bounds__(64 * kGramWaves) gram_mfma_kernel(const float*
     for (int t = 0; t < TPW; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     const int nchunks = (nb + kRowsPerChunk - 1) / kRowsPerChunk;
-    float v[kRowsPerChunk][CL];
+    float v[kRowsPerChunk][CL];                      // (not VEC)
     float yv = 0.f;
+    // VEC: the 16 * p / 4 float4 of a chunk are dealt to the lanes in turn; which row and which columns lane l's i-th
+    // float4 belongs to does not change from chunk to chunk
+    constexpr int NV = WIDE ? 8 : 4;                 // float4 per lane and chunk: 16 * (p / 4) / 64 rounded up for the largest p
+    float4 v4[VEC ? NV : 1];
+    int vrow[VEC ? NV : 1], vcol[VEC ? NV : 1];      // row of the chunk (as a byte offset of its lane for the shuffle), first column
+    if constexpr (VEC) {
+        const int p4 = p >> 2;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int e = min(lane + 64 * i, kRowsPerChunk * p4 - 1);    // (beyond the chunk: the last float4 again, same value)
+            const int r = e / p4;
+            vrow[i] = r;
+            vcol[i] = 4 * (e - r * p4);
+        }
+    }
     auto request = [&](int chunk) {
-        // unconditional loads from clamped rows and columns; what lies outside the mini-batch is zeroed on use
-        const int i = min(chunk * kRowsPerChunk + (lane & 15), nb - 1);
-        const int row = idx[i];
-        yv = y[row];
+        if constexpr (VEC) {
+            const int i = min(chunk * kRowsPerChunk + (lane & 15), nb - 1);
+            const int row = idx[i];
+            yv = y[row];
 #pragma unroll
-        for (int r = 0; r < kRowsPerChunk; ++r) {
-            const int rr = __builtin_amdgcn_readlane(row, r);
-            const float* src = X + (size_t)rr * p;
+            for (int q = 0; q < NV; ++q) {
+                const int rr = __builtin_amdgcn_ds_bpermute(4 * vrow[q], row);   // the row index held by lane vrow[q]
+                v4[q] = *reinterpret_cast<const float4*>(X + (size_t)rr * p + vcol[q]);
+            }
+        } else {
+            // unconditional loads from clamped rows and columns; what lies outside the mini-batch is zeroed on use
+            const int i = min(chunk * kRowsPerChunk + (lane & 15), nb - 1);
+            const int row = idx[i];
+            yv = y[row];
 #pragma unroll
-            for (int j = 0; j < CL; ++j) v[r][j] = src[min(lane + 64 * j, p - 1)];
+            for (int r = 0; r < kRowsPerChunk; ++r) {
+                const int rr = __builtin_amdgcn_readlane(row, r);
+                const float* src = X + (size_t)rr * p;
+#pragma unroll
+                for (int j = 0; j < CL; ++j) v[r][j] = src[min(lane + 64 * j, p - 1)];
+            }
         }
     };
     auto stage = [&](int chunk) {
         const int left = nb - chunk * kRowsPerChunk;              // rows of this chunk inside the mini-batch
+        if constexpr (VEC) {
+            if (left < kRowsPerChunk) {                           // (uniform) the last chunk: rows beyond the mini-batch are zeroed
 #pragma unroll
-        for (int r = 0; r < kRowsPerChunk; ++r) {
-#pragma unroll
-            for (int j = 0; j < CL; ++j) {
-                // no branch: lanes beyond p write a zero into a padding column (or into the column of y, which
-                // the store below then overwrites)
-                const int c = lane + 64 * j;
-                xs[r * stride + min(c, stride - 1)] = (c < p && r < left) ? v[r][j] : 0.f;
+                for (int q = 0; q < NV; ++q)
+                    if (vrow[q] >= left) v4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
+#pragma unroll
+            for (int q = 0; q < NV; ++q) *reinterpret_cast<float4*>(xs + vrow[q] * stride + vcol[q]) = v4[q];
+            __builtin_amdgcn_wave_barrier();
+            if (lane < kRowsPerChunk) xs[lane * stride + p] = lane < left ? yv : 0.f;
+        } else {
+#pragma unroll
+            for (int r = 0; r < kRowsPerChunk; ++r) {
+#pragma unroll
+                for (int j = 0; j < CL; ++j) {
+                    // no branch: lanes beyond p write a zero into a padding column (or into the column of y, which
+                    // the store below then overwrites)
+                    const int c = lane + 64 * j;
+                    xs[r * stride + min(c, stride - 1)] = (c < p && r < left) ? v[r][j] : 0.f;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane < kRowsPerChunk) xs[lane * stride + p] = lane < left ? yv : 0.f;
         }
-        __builtin_amdgcn_wave_barrier();
-        if (lane < kRowsPerChunk) xs[lane * stride + p] = lane < left ? yv : 0.f;
     };
 
     if (wave < nchunks) request(wave);
@@ -294,12 +334,15 @@ hipError_t launch_gram_mfma(bool wide, dim3 grid, size_t lds, hipStream_t stream
                             const GramTiles& T, int dense_q, hipEvent_t start, hipEvent_t stop)
 {
     // the events ride on the dispatch itself: no separate markers in the queue
-    if (wide)
-        hipExtLaunchKernelGGL((gram_mfma_kernel<TPW, true>), grid, dim3(64 * kGramWaves), (uint32_t)lds, stream, start, stop, 0u, X,
-                              y, perm, out, rows, n, perm_stride, M, n_items, stride, L, T, dense_q);
-    else
-        hipExtLaunchKernelGGL((gram_mfma_kernel<TPW, false>), grid, dim3(64 * kGramWaves), (uint32_t)lds, stream, start, stop, 0u, X,
-                              y, perm, out, rows, n, perm_stride, M, n_items, stride, L, T, dense_q);
+    const bool vec = L.p % 4 == 0;
+#define GRAM_LAUNCH(W, V)                                                                                                          \
+    hipExtLaunchKernelGGL((gram_mfma_kernel<TPW, W, V>), grid, dim3(64 * kGramWaves), (uint32_t)lds, stream, start, stop, 0u, X, y,  \
+                          perm, out, rows, n, perm_stride, M, n_items, stride, L, T, dense_q)
+    if (wide && vec) GRAM_LAUNCH(true, true);
+    else if (wide) GRAM_LAUNCH(true, false);
+    else if (vec) GRAM_LAUNCH(false, true);
+    else GRAM_LAUNCH(false, false);
+#undef GRAM_LAUNCH
     return hipGetLastError();
 }
 

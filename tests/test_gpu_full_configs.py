@@ -30,9 +30,11 @@ def test_cfg2_whole_run():
     w = wl.CONFIGS["cfg2"]
     X, y = wl.dataset(w)
     want = oracle_run(w, X, y)
-    for chain in (0, 1):                                       # automatic (the form of eq. (3.1)), then the row form
+    # automatic (the form of eq. (3.1) with steps multiplied in pairs: 300 steps per launch), the plain chain of eq. (3.1),
+    # the row form
+    for chain in (0, 3, 1):
         got, st = gpu_run(w, X, y, resident=True, chain=chain)
-        assert st.chain == (3 if chain == 0 else 1)
+        assert st.chain == {0: 5, 3: 3, 1: 1}[chain]
         assert st.steps == 15_000 and st.sample_gradients == 15_000_000
         assert rel_l2(got, want) <= TOL_F32
         assert np.linalg.norm(got - wl.true_theta(w)) < 0.15  # and it has learnt the coefficients

@@ -20,7 +20,7 @@ def test_cfg1_full_run():
     w = wl.CONFIGS["cfg1"]
     X, y = wl.dataset(w)
     want = oracle_run(w, X, y)
-    for chain in (0, 1):                                # 0: automatic (the form of eq. (3.1) here), 1: row form
+    for chain in (0, 1):                                # 0: automatic (the chain of eq. (3.1) here: 40 steps per launch), 1: row form
         got, st = gpu_run(w, X, y, chain=chain)
         assert st.chain == (3 if chain == 0 else 1)
         assert st.steps == w.steps and st.sample_gradients == w.sample_gradients
